@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5] [--no-extra] [--no-cpu]
+
+A step is one call of the library on one synthetic batch with every input resident in HBM.
+The headline line is the Llama-3-8B-shaped paged decode (config 2), reported as algorithmic
+HBM GB/s; the same JSON line carries the other configurations (varlen prefill, chunked prefill,
+long-context decode) under "extra", each with its own roofline figure, and the fp64 CPU oracle
+timed on the host's cores under "cpu_baseline".  Inputs are seeded synthetic stand-ins for the
+paper's unpublished length samples (see workloads.py).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+
+WORKLOADS = {"c2": 2, "c3": 3, "c4": 4, "c5": 5}
+
+
+def _dev(a):
+    import torch
+
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
+    return torch.from_numpy(a).cuda()
+
+
+class Runner:
+    """Holds one workload on the device and enqueues one step per call."""
+
+    def __init__(self, wl, pools: int = 1):
+        import torch
+
+        import paper_2505_03780_amd as A
+
+        self.A, self.torch, self.wl = A, torch, wl
+        self.is_decode = wl.kind == "decode"
+        self.q = _dev(wl.q)
+        self.out = torch.zeros_like(self.q)
+        k, v = _dev(wl.k), _dev(wl.v)
+        # decode streams the KV cache once per step: alternate between distinct copies of the pool so
+        # that a step never finds its keys in the last-level cache left over from the previous step
+        self.kv = [(k, v)] + [(k.clone(), v.clone()) for _ in range(pools - 1)]
+        self.qsl = torch.from_numpy(wl.query_start_loc).cuda()
+        self.sl = torch.from_numpy(wl.seq_lens).cuda()
+        self.bt = None if wl.block_table is None else torch.from_numpy(wl.block_table).cuda()
+        self.kvsl = None if wl.kv_start_loc is None else torch.from_numpy(wl.kv_start_loc).cuda()
+        self.max_q = 1 if self.is_decode else int(wl.q_lens().max())
+        self.max_kv = int(wl.seq_lens.max())
+        self.args = []
+        self.ws = None
+        for (kk, vv) in self.kv:
+            a = A.make_args(self.q, kk, vv, self.out, self.sl, wl.scale, max_q_len=self.max_q, max_kv_len=self.max_kv,
+                            query_start_loc=None if self.is_decode else self.qsl, kv_start_loc=self.kvsl,
+                            block_table=self.bt, causal=wl.causal, is_decode=self.is_decode)
+            if self.is_decode:
+                if self.ws is None:
+                    self.ws = torch.empty(max(A.attn_workspace_bytes(a, True) // 4, 4), dtype=torch.float32, device="cuda")
+                a.workspace = self.ws.data_ptr()
+                a.workspace_bytes = self.ws.numel() * 4
+            self.args.append(a)
+        self.lib = A.load_library()
+        self.fn = self.lib.attn_decode_paged if self.is_decode else self.lib.attn_prefill_varlen
+        self.i = 0
+        self.instance = A.attn_instance_name(self.is_decode, A.attn_selected_instance(self.args[0], self.is_decode))
+
+    def step(self, stream_ptr):
+        a = self.args[self.i % len(self.args)]
+        self.i += 1
+        rc = self.fn(a, stream_ptr)
+        if rc != 0:
+            raise RuntimeError("library call failed: %s" % self.A.attn_status_string(rc))
+
+
+def time_steps(run: Runner, steps: int, warmup: int):
+    """Returns (wall ms per step over the whole timed region, mean ms of per-step HIP event pairs)."""
+    torch = run.torch
+    stream = torch.cuda.current_stream()
+    sp = stream.cuda_stream
+    for _ in range(warmup):
+        run.step(sp)
+    torch.cuda.synchronize()
+    # per-step event pairs on the launch stream: the duration of one step's kernels
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for a, b in ev:
+        a.record(stream)
+        run.step(sp)
+        b.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    per = np.array([a.elapsed_time(b) for a, b in ev])
+    return wall_ms, float(per.mean()), float(np.median(per))
+
+
+def measure(wl_id: int, steps: int, warmup: int, tune: bool):
+    import workloads as W
+
+    wl = W.CONFIGS[wl_id]()
+    run = Runner(wl, pools=2 if wl.kind == "decode" else 1)
+    if tune:
+        run.A.attn_tune(run.args[0], run.is_decode, os.environ.get("ATTN_TUNE_CACHE"), 10, 0)
+        run.instance = run.A.attn_instance_name(run.is_decode, run.A.attn_selected_instance(run.args[0], run.is_decode))
+    wall_ms, ev_mean_ms, ev_med_ms = time_steps(run, steps, warmup)
+    res = {"workload": wl.name, "instance": run.instance, "ms_per_step": wall_ms, "kernel_ms_mean": ev_mean_ms,
+           "kernel_ms_median": ev_med_ms}
+    if wl.kind == "decode":
+        nbytes = wl.algorithmic_bytes()
+        ach = nbytes / (ev_mean_ms * 1e-3) / 1e9
+        res.update(metric="decode_hbm_GBps", unit="GB/s", value=nbytes / (wall_ms * 1e-3) / 1e9, algorithmic_bytes=nbytes,
+                   roofline={"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                             "frac": ach / HBM_PEAK_GBPS, "traffic": None})
+    else:
+        fl = wl.flops()
+        ach = fl / (ev_mean_ms * 1e-3) / 1e12
+        res.update(metric="prefill_TFLOPs", unit="TFLOP/s", value=fl / (wall_ms * 1e-3) / 1e12, algorithmic_flops=fl,
+                   roofline={"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                             "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None})
+    return wl, res
+
+
+def cpu_baseline(wl, unit: str):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload (about 10-30 s of CPU)."""
+    import oracle
+
+    prob = oracle.OracleProblem(wl.q, wl.k, wl.v, wl.query_start_loc, wl.seq_lens, wl.scale, wl.causal,
+                                block_table=wl.block_table, kv_start_loc=wl.kv_start_loc)
+    nq = wl.q_lens()
+    # sample: whole (sequence, head) rows until about 4 GFLOP of oracle work is collected
+    budget = 4e9
+    seqs, toks, heads = [], [], []
+    flops = 0.0
+    nbytes = 0.0
+    rng = np.random.default_rng(0)
+    order = rng.permutation(wl.num_seqs)
+    for s in order:
+        for h in range(wl.num_q_heads):
+            if flops >= budget:
+                break
+            off = int(wl.seq_lens[s] - nq[s])
+            t = np.arange(nq[s])
+            seqs.append(np.full(nq[s], s)); toks.append(t); heads.append(np.full(nq[s], h))
+            pairs = float(np.sum(off + t + 1)) if wl.causal else float(nq[s] * wl.seq_lens[s])
+            flops += 4.0 * wl.head_dim * pairs
+            nbytes += float(wl.seq_lens[s]) * wl.head_dim * 2 * 2 / (wl.num_q_heads // wl.num_kv_heads)
+    seqs, toks, heads = (np.concatenate(x).astype(np.int32) for x in (seqs, toks, heads))
+    oracle.attention_rows(prob, seqs[:8], toks[:8], heads[:8])  # load the library, touch the data
+    t0 = time.perf_counter()
+    oracle.attention_rows(prob, seqs, toks, heads)
+    dt = time.perf_counter() - t0
+    val = (nbytes / dt / 1e9) if unit == "GB/s" else (flops / dt / 1e12)
+    return {"value": val, "unit": unit, "cores": oracle.num_threads(), "kind": "oracle", "seconds": dt,
+            "sample": "%d output rows (%d whole (sequence, head) pairs, %.2f GFLOP of the workload's %.2f) of %s" % (
+                len(seqs), len(np.unique(seqs * 1000 + heads)), flops / 1e9, wl.flops() / 1e9, wl.name)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", choices=sorted(WORKLOADS), default="c2")
+    ap.add_argument("--no-extra", action="store_true", help="skip the other configurations")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--tune", action="store_true", help="run attn_tune for each bucket first (untimed)")
+    a = ap.parse_args()
+    if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU only (one MI355X, no collectives); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+
+    wl, main_res = measure(WORKLOADS[a.workload], a.steps, a.warmup, a.tune)
+    line = {
+        "metric": main_res["metric"], "value": main_res["value"], "unit": main_res["unit"], "n_gpus": 1,
+        "steps": a.steps, "warmup": a.warmup, "ms_per_step": main_res["ms_per_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "instance": main_res["instance"], "num_seqs": wl.num_seqs,
+                   "num_q_heads": wl.num_q_heads, "num_kv_heads": wl.num_kv_heads, "head_dim": wl.head_dim,
+                   "kv_block_size": wl.block_size, "kv_tokens": int(wl.seq_lens.sum()), "tuned": bool(a.tune)},
+        "kernel_ms_mean": main_res["kernel_ms_mean"], "kernel_ms_median": main_res["kernel_ms_median"],
+        "roofline": main_res["roofline"],
+    }
+    if not a.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(wl, main_res["unit"])
+    del wl
+    if not a.no_extra:
+        extra = {}
+        for name, wid in sorted(WORKLOADS.items()):
+            if name == a.workload:
+                continue
+            torch.cuda.empty_cache()
+            _, r = measure(wid, max(5, a.steps // 2), max(2, a.warmup // 2), a.tune)
+            extra[name] = {k: r[k] for k in ("workload", "instance", "metric", "value", "unit", "ms_per_step", "kernel_ms_mean", "roofline")}
+        line["extra"] = extra
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

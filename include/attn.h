@@ -1,0 +1,164 @@
+/*
+ * attn.h -- C ABI of the MI355X (gfx950) fused-attention library.
+ *
+ * The library computes exact scaled-dot-product attention for LLM inference,
+ * the kernel the paper uses as its main vehicle (section "Method and
+ * Investigated Kernels": flash attention, Llama3-8B shapes -- head size 128,
+ * 32 query heads, 8 KV heads -- with sequences of different lengths in one
+ * batch; Fig. 2: causal).  For every sequence s, query head h and new-token
+ * index i it returns
+ *
+ *     out[i,h,:] = sum_j softmax_j( scale * q[i,h,:] . k[j,h/G,:] ) * v[j,h/G,:]
+ *
+ * over the keys j visible to query i, with G = num_q_heads / num_kv_heads
+ * (consecutive query heads share a KV head).  The paper states no interface;
+ * the argument names follow its problem statement (Q, K, V, block table,
+ * sequence lengths, query start offsets, softmax scale).
+ *
+ * Conventions
+ *  - Every pointer in attn_args is a DEVICE pointer owned by the caller and must
+ *    stay valid until the work queued on the stream has finished.  The host
+ *    never dereferences them.  Strides are in ELEMENTS; head_dim is contiguous.
+ *  - attn_prefill_varlen and attn_decode_paged only validate host-visible
+ *    fields, look up a kernel instance and enqueue kernels on `hip_stream`
+ *    (a hipStream_t passed as void*; NULL = the default stream).  They do not
+ *    allocate, free, synchronise or copy, so they may be captured in a HIP graph
+ *    (the paper times its kernels under CUDA/HIP graphs, same section).
+ *  - Errors that the host can see are returned as a negative attn_status and
+ *    nothing is enqueued.  Out-of-range block_table entries, or seq_lens /
+ *    query_start_loc that disagree with total_q, max_q_len, max_kv_len, are
+ *    undefined behaviour.
+ *  - Hot calls are re-entrant; the winner cache is guarded by a mutex.
+ */
+#ifndef ATTN_H_
+#define ATTN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum attn_status {
+    ATTN_OK = 0,
+    ATTN_ERR_NULL = -1,        /* a required pointer is NULL */
+    ATTN_ERR_SHAPE = -2,       /* inconsistent sizes, strides or head counts */
+    ATTN_ERR_DTYPE = -3,       /* dtype not supported by this entry point */
+    ATTN_ERR_UNSUPPORTED = -4, /* head_dim / block_size / group size without a kernel instance */
+    ATTN_ERR_WORKSPACE = -5,   /* workspace missing or smaller than attn_workspace_bytes() */
+    ATTN_ERR_HIP = -6,         /* the HIP runtime refused a launch or an allocation */
+    ATTN_ERR_CACHE_IO = -7     /* the tuning cache file could not be read or written */
+} attn_status;
+
+typedef enum attn_dtype {
+    ATTN_F32 = 0, /* q, k, v, out are IEEE fp32; arithmetic is fp32 FMA */
+    ATTN_BF16 = 1 /* q, k, v, out are bfloat16; products on bf16 MFMA, fp32 accumulation and softmax */
+} attn_dtype;
+
+typedef struct attn_args {
+    uint32_t struct_bytes; /* = sizeof(attn_args); calls with another value are rejected */
+    int32_t dtype;         /* attn_dtype of q, k, v and out */
+    int32_t num_seqs;      /* B */
+    int32_t num_q_heads;   /* Hq */
+    int32_t num_kv_heads;  /* Hkv, divides Hq */
+    int32_t head_dim;      /* D: 64 or 128 */
+    int32_t total_q;       /* host copy of query_start_loc[B]; decode: = B */
+    int32_t max_q_len;     /* host upper bound of n_q(s); sizes the grid, no device sync needed */
+    int32_t max_kv_len;    /* host upper bound of seq_lens[s] */
+
+    const void *q; /* [total_q, Hq, D] */
+    int64_t q_stride_tok, q_stride_head;
+    void *out; /* [total_q, Hq, D], same dtype as q */
+    int64_t o_stride_tok, o_stride_head;
+
+    /* contiguous mode (block_table == NULL): k, v are [total_kv, Hkv, D] and key j of sequence s
+     * is row kv_start_loc[s] + j.  paged mode: k, v are [num_blocks, block_size, Hkv, D] and key j
+     * of sequence s is slot j % block_size of block block_table[s][j / block_size]. */
+    const void *k;
+    const void *v;
+    int64_t kv_stride_block, kv_stride_tok, kv_stride_head;
+
+    const int32_t *block_table; /* int32 [B, block_table_stride]; entries past ceil(seq_len/block_size) are never read */
+    int32_t block_table_stride;
+    int32_t block_size; /* paged: a multiple of 16 */
+    int32_t num_blocks; /* pool size, used only for validation */
+
+    const int32_t *query_start_loc; /* int32 [B+1], exclusive prefix sum of n_q; decode: ignored (n_q = 1) */
+    const int32_t *kv_start_loc;    /* int32 [B+1], contiguous mode only; NULL -> query_start_loc */
+    const int32_t *seq_lens;        /* int32 [B]: keys of sequence s = cached prefix + new tokens, already stored */
+
+    float scale;    /* softmax scale applied to q.k (1/sqrt(D) for standard attention) */
+    int32_t causal; /* 1: query i sees keys j <= (seq_lens[s] - n_q(s)) + i (bottom-right aligned); 0: all keys */
+
+    void *workspace; /* device scratch for split-K partials; may be NULL if attn_workspace_bytes() == 0 */
+    uint64_t workspace_bytes;
+} attn_args;
+
+/*
+ * Causal variable-length prefill, also over a paged prefix (chunked prefill).
+ * Tiled online-softmax attention in the FlashAttention-2 formulation the paper
+ * builds on (same section; Fig. 2 "causal flash attention"): the score matrix
+ * is never materialised.  Sequences with n_q = 0 write nothing.  A query with
+ * no visible key (possible only when causal == 0 and seq_len == 0) gets zeros.
+ * dtype ATTN_BF16 (D = 128 or 64) or ATTN_F32 (D = 64 or 128).
+ * Returns ATTN_OK after enqueueing, or a negative attn_status.
+ */
+int attn_prefill_varlen(const attn_args *args, void *hip_stream);
+
+/*
+ * Paged-KV decode: one query token per sequence (q is [B, Hq, D]) attending to
+ * all seq_lens[s] keys held in the paged cache addressed by block_table (the
+ * paper cites PagedAttention for this setting; layout above).  Long contexts
+ * are split along the key axis; each part writes an fp32 (max, sum, partial
+ * output) triple into `workspace` and a second kernel merges them.  The caller
+ * provides at least attn_workspace_bytes(args, 1) bytes.  bf16 only.
+ */
+int attn_decode_paged(const attn_args *args, void *hip_stream);
+
+/*
+ * Bytes of workspace the call described by `args` may use (pure host function;
+ * pointer fields are ignored).  is_decode = 1 for attn_decode_paged.
+ * Returns 0 when args is NULL or malformed.
+ */
+size_t attn_workspace_bytes(const attn_args *args, int is_decode);
+
+/*
+ * Ahead-of-time autotuning (the paper's requirements list: tune off the
+ * critical path, keep results in a reusable cache that records its
+ * environment).  Times every valid compiled kernel instance for the shape
+ * bucket of `shape_like` on synthetic device buffers that this call allocates
+ * and frees itself (pointer fields of shape_like are ignored; lengths are
+ * spread uniformly up to max_q_len / max_kv_len), records the fastest, and, if
+ * cache_path is not NULL, merges it into that file (atomic replace).  `iters`
+ * timed launches per instance (<= 0: a default).  Synchronous; not capturable.
+ * flags: bit 0 = print one line per instance to stderr.
+ */
+int attn_tune(const attn_args *shape_like, int is_decode, const char *cache_path, int iters, int flags);
+
+/* Load winners from a cache file written by attn_tune.  Entries recorded for a different device,
+ * CU count or library build are skipped.  Also done lazily from $ATTN_TUNE_CACHE on the first hot
+ * call.  A missing or corrupt file returns ATTN_ERR_CACHE_IO and leaves the built-in heuristic in
+ * force; hot calls never fail because of the cache. */
+int attn_load_cache(const char *cache_path);
+
+/* Forget all cached winners (hot calls fall back to the built-in heuristic). */
+void attn_clear_cache(void);
+
+/* Introspection for the tuner and the tests (pure host functions). */
+int attn_num_instances(int is_decode);
+/* Writes a NUL-terminated description ("prefill_bf16 bm=.. bn=.. ...") of instance `id`;
+ * returns its length, or a negative attn_status for a bad id. */
+int attn_instance_name(int is_decode, int id, char *buf, size_t buf_bytes);
+/* Instance the next hot call with these args would launch (cache winner, else heuristic), or <0. */
+int attn_selected_instance(const attn_args *args, int is_decode);
+/* Force an instance id for all later hot calls of that kind (-1 = back to automatic).  Invalid
+ * combinations are rejected by the hot call with ATTN_ERR_UNSUPPORTED. */
+void attn_force_instance(int is_decode, int id);
+
+const char *attn_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ATTN_H_ */

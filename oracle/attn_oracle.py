@@ -50,11 +50,12 @@ class _CProblem(ctypes.Structure):
 
 
 def build(force: bool = False) -> str:
-    """Compile the C oracle with gcc (strict IEEE arithmetic, OpenMP over rows)."""
+    """Compile the C oracle with gcc: strict IEEE arithmetic, no FMA contraction, baseline x86-64
+    (the library may be built on one host and run on another), OpenMP over rows."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp.%d" % os.getpid()
         subprocess.check_call(
-            ["gcc", "-O2", "-march=native", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-o", tmp, _SRC, "-lm"]
+            ["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-o", tmp, _SRC, "-lm"]
         )
         os.replace(tmp, _LIB)
     return _LIB

@@ -1,0 +1,604 @@
+// C ABI of the attention library: argument validation, shape buckets, instance
+// selection (winner cache, else heuristic), the in-library autotuner and its
+// persistent cache.
+//
+// The tuner is the paper's thesis applied natively: instead of JIT-compiling
+// configurations at first call, every configuration is a template instance
+// compiled ahead of time; attn_tune times the valid ones for a shape bucket off
+// the critical path and stores the winner, together with the environment it was
+// measured in, in a file that later processes load (the paper's list of gaps
+// towards practical autotuning: configuration spaces with parameter
+// dependencies, reusable caches that record their environment, tuning moved off
+// the critical path).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <atomic>
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <fstream>
+#include <mutex>
+#include <sstream>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include <unistd.h>
+
+#include "../../include/attn.h"
+#include "kernel_params.hpp"
+
+namespace attn {
+namespace {
+
+constexpr const char *kCacheMagic = "attn-tune-cache-v1";
+// Changes whenever the kernels change in a way that invalidates old timings.
+constexpr const char *kBuildId = "k1";
+constexpr int kMinSplitLen = 256;
+
+std::mutex g_mu;
+std::unordered_map<std::string, int> g_winner[2];  // [is_decode]: bucket key -> instance id
+std::atomic<int> g_forced[2] = {{-1}, {-1}};
+bool g_env_cache_tried = false;
+
+const Instance *instances(int is_decode, int *n) { return is_decode ? decode_instances(n) : prefill_instances(n); }
+
+int ilog2_ceil(int64_t x)
+{
+    int r = 0;
+    while (((int64_t)1 << r) < x) ++r;
+    return r;
+}
+
+// ---- validation --------------------------------------------------------------------------------
+
+int validate(const attn_args *a, int is_decode)
+{
+    if (!a) return ATTN_ERR_NULL;
+    if (a->struct_bytes != sizeof(attn_args)) return ATTN_ERR_SHAPE;
+    if (a->dtype != ATTN_F32 && a->dtype != ATTN_BF16) return ATTN_ERR_DTYPE;
+    if (is_decode && a->dtype != ATTN_BF16) return ATTN_ERR_DTYPE;
+    if (a->num_seqs < 0 || a->num_q_heads <= 0 || a->num_kv_heads <= 0 || a->total_q < 0 || a->max_q_len < 0 ||
+        a->max_kv_len < 0)
+        return ATTN_ERR_SHAPE;
+    if (a->num_q_heads % a->num_kv_heads != 0) return ATTN_ERR_SHAPE;
+    if (a->head_dim != 64 && a->head_dim != 128) return ATTN_ERR_UNSUPPORTED;
+    if (is_decode && a->total_q != a->num_seqs) return ATTN_ERR_SHAPE;
+    if (is_decode && a->max_q_len > 1) return ATTN_ERR_SHAPE;
+    const int vec = a->dtype == ATTN_BF16 ? 8 : 1;  // elements per 16-byte vector access
+    if (a->q_stride_head < a->head_dim || a->o_stride_head < a->head_dim || a->kv_stride_head < a->head_dim ||
+        a->q_stride_tok <= 0 || a->o_stride_tok <= 0 || a->kv_stride_tok <= 0)
+        return ATTN_ERR_SHAPE;
+    if (a->q_stride_tok % vec || a->q_stride_head % vec || a->o_stride_tok % vec || a->o_stride_head % vec ||
+        a->kv_stride_tok % vec || a->kv_stride_head % vec)
+        return ATTN_ERR_SHAPE;
+    if (a->block_table) {
+        if (a->block_size < 16 || (a->block_size & (a->block_size - 1)) != 0) return ATTN_ERR_UNSUPPORTED;
+        if (a->block_table_stride <= 0 || a->num_blocks <= 0 || a->kv_stride_block <= 0 || a->kv_stride_block % vec)
+            return ATTN_ERR_SHAPE;
+        if ((int64_t)a->block_table_stride * a->block_size < a->max_kv_len) return ATTN_ERR_SHAPE;
+    } else if (is_decode) {
+        return ATTN_ERR_NULL;  // decode is paged only
+    }
+    if (a->num_seqs == 0 || a->total_q == 0) return ATTN_OK;  // nothing to do; pointers may be NULL
+    if (!a->q || !a->out || !a->seq_lens) return ATTN_ERR_NULL;
+    if (a->max_kv_len > 0 && (!a->k || !a->v)) return ATTN_ERR_NULL;
+    if (!is_decode && !a->query_start_loc) return ATTN_ERR_NULL;
+    if (a->dtype == ATTN_BF16) {
+        const uintptr_t bits = (uintptr_t)a->q | (uintptr_t)a->out | (uintptr_t)a->k | (uintptr_t)a->v;
+        if (bits & 15) return ATTN_ERR_SHAPE;  // 128-bit accesses
+    }
+    return ATTN_OK;
+}
+
+KParams to_kparams(const attn_args *a, int is_decode)
+{
+    KParams p{};
+    p.q = a->q;
+    p.out = a->out;
+    p.k = a->k;
+    p.v = a->v;
+    p.block_table = a->block_table;
+    p.query_start_loc = is_decode ? nullptr : a->query_start_loc;
+    p.kv_start_loc = a->kv_start_loc ? a->kv_start_loc : a->query_start_loc;
+    p.seq_lens = a->seq_lens;
+    p.q_stride_tok = a->q_stride_tok;
+    p.q_stride_head = a->q_stride_head;
+    p.o_stride_tok = a->o_stride_tok;
+    p.o_stride_head = a->o_stride_head;
+    p.kv_stride_block = a->kv_stride_block;
+    p.kv_stride_tok = a->kv_stride_tok;
+    p.kv_stride_head = a->kv_stride_head;
+    p.num_seqs = a->num_seqs;
+    p.num_q_heads = a->num_q_heads;
+    p.num_kv_heads = a->num_kv_heads;
+    p.head_dim = a->head_dim;
+    p.group = a->num_q_heads / a->num_kv_heads;
+    p.block_table_stride = a->block_table_stride;
+    p.block_size = a->block_table ? a->block_size : 0;
+    p.block_shift = a->block_table ? ilog2_ceil(a->block_size) : 0;
+    p.max_q_len = is_decode ? 1 : a->max_q_len;
+    p.max_kv_len = a->max_kv_len;
+    p.scale = a->scale;
+    p.scale_log2e = a->scale * 1.4426950408889634f;
+    p.causal = a->causal ? 1 : 0;
+    p.workspace = (float *)a->workspace;
+    p.num_splits = 1;
+    p.split_len = 0;
+    return p;
+}
+
+// ---- shape buckets ------------------------------------------------------------------------------
+// A bucket fixes everything a kernel instance is specialised on and rounds the three extents
+// (sequences, longest query, longest context) up to powers of two.
+std::string bucket_key(const KParams &p, int dtype, int is_decode)
+{
+    char buf[192];
+    snprintf(buf, sizeof buf, "%s|%s|d%d|hq%d|hkv%d|%s|bs%d|c%d|B%d|q%d|kv%d", is_decode ? "decode" : "prefill",
+             dtype == ATTN_BF16 ? "bf16" : "f32", p.head_dim, p.num_q_heads, p.num_kv_heads,
+             p.block_table ? "paged" : "contig", p.block_size, p.causal, ilog2_ceil(std::max(1, p.num_seqs)),
+             ilog2_ceil(std::max(1, p.max_q_len)), ilog2_ceil(std::max(1, p.max_kv_len)));
+    return buf;
+}
+
+void apply_split(KParams &p, const Instance &inst)
+{
+    int sl = inst.split_len;
+    if (sl <= 0 || sl >= p.max_kv_len) {
+        p.split_len = std::max(p.max_kv_len, 1);
+        p.num_splits = 1;
+    } else {
+        p.split_len = sl;
+        p.num_splits = (p.max_kv_len + sl - 1) / sl;
+    }
+}
+
+// ---- built-in heuristic (used until a bucket has been tuned) -----------------------------------
+int find_instance(int is_decode, const KParams &p, int waves, int hpw, int bn, int bm, int split_len)
+{
+    int n;
+    const Instance *t = instances(is_decode, &n);
+    for (int i = 0; i < n; ++i) {
+        if (!t[i].valid(p)) continue;
+        if (t[i].waves == waves && t[i].heads_per_wg == hpw && t[i].block_n == bn && (bm <= 0 || t[i].block_m == bm) &&
+            t[i].split_len == split_len)
+            return i;
+    }
+    return -1;
+}
+
+int heuristic(const KParams &p, int is_decode)
+{
+    int n;
+    const Instance *t = instances(is_decode, &n);
+    int id = -1;
+    if (!is_decode) {
+        // pack as many heads of a KV head as divide the group: they share every K/V tile
+        int hpw = p.group % 4 == 0 ? 4 : (p.group % 2 == 0 ? 2 : 1);
+        id = find_instance(0, p, 4, hpw, 64, 64 * 4, 0);
+    } else {
+        // enough workgroups to fill 256 CUs several times over, but parts no shorter than 256 keys
+        const int64_t units = (int64_t)p.num_seqs * p.num_kv_heads;
+        int64_t want = units * (int64_t)p.max_kv_len / 2048;
+        int sl = kMinSplitLen;
+        while (sl * 2 <= want && sl < 4096) sl *= 2;
+        if (sl >= p.max_kv_len) sl = 0;
+        id = find_instance(1, p, 4, 16, 32, 0, sl);
+        if (id < 0) id = find_instance(1, p, 4, 16, 32, 0, 0);
+    }
+    if (id >= 0) return id;
+    for (int i = 0; i < n; ++i)
+        if (t[i].valid(p)) return i;
+    return -1;
+}
+
+// ---- environment key and cache file ------------------------------------------------------------
+std::string environment_key()
+{
+    hipDeviceProp_t prop;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return std::string("nodevice|cu0|") + kBuildId;
+    }
+    int rt = 0;
+    (void)hipRuntimeGetVersion(&rt);
+    std::ostringstream os;
+    os << prop.gcnArchName << "|cu" << prop.multiProcessorCount << "|hip" << rt << "|" << kBuildId;
+    return os.str();
+}
+
+int instance_by_name(int is_decode, const std::string &name)
+{
+    int n;
+    const Instance *t = instances(is_decode, &n);
+    for (int i = 0; i < n; ++i)
+        if (name == t[i].name) return i;
+    return -1;
+}
+
+struct CacheLine {
+    std::string env, key, inst;
+    double us;
+};
+
+bool parse_line(const std::string &line, CacheLine *out)
+{
+    // fields separated by tabs: env, bucket key, instance name, microseconds
+    std::vector<std::string> f;
+    size_t pos = 0;
+    while (true) {
+        size_t t = line.find('\t', pos);
+        f.push_back(line.substr(pos, t == std::string::npos ? std::string::npos : t - pos));
+        if (t == std::string::npos) break;
+        pos = t + 1;
+    }
+    if (f.size() != 4) return false;
+    char *end = nullptr;
+    double us = strtod(f[3].c_str(), &end);
+    if (end == f[3].c_str() || !(us >= 0)) return false;
+    *out = CacheLine{f[0], f[1], f[2], us};
+    return true;
+}
+
+int read_cache_file(const char *path, std::vector<CacheLine> *lines)
+{
+    std::ifstream in(path);
+    if (!in) return ATTN_ERR_CACHE_IO;
+    std::string line;
+    if (!std::getline(in, line) || line != kCacheMagic) return ATTN_ERR_CACHE_IO;
+    while (std::getline(in, line)) {
+        if (line.empty() || line[0] == '#') continue;
+        CacheLine cl;
+        if (!parse_line(line, &cl)) return ATTN_ERR_CACHE_IO;
+        lines->push_back(cl);
+    }
+    return ATTN_OK;
+}
+
+int load_cache_locked(const char *path)
+{
+    std::vector<CacheLine> lines;
+    int rc = read_cache_file(path, &lines);
+    if (rc != ATTN_OK) return rc;
+    const std::string env = environment_key();
+    for (const CacheLine &cl : lines) {
+        if (cl.env != env) continue;  // measured on another device or library build
+        const int is_decode = cl.key.compare(0, 6, "decode") == 0;
+        const int id = instance_by_name(is_decode, cl.inst);
+        if (id < 0) continue;
+        g_winner[is_decode][cl.key] = id;
+    }
+    return ATTN_OK;
+}
+
+void maybe_load_env_cache()
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (g_env_cache_tried) return;
+    g_env_cache_tried = true;
+    const char *path = getenv("ATTN_TUNE_CACHE");
+    if (path && *path) (void)load_cache_locked(path);
+}
+
+int select_instance(const KParams &p, int dtype, int is_decode)
+{
+    int n;
+    const Instance *t = instances(is_decode, &n);
+    const int forced = g_forced[is_decode].load();
+    if (forced >= 0) return forced < n && t[forced].valid(p) ? forced : ATTN_ERR_UNSUPPORTED;
+    maybe_load_env_cache();
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        auto it = g_winner[is_decode].find(bucket_key(p, dtype, is_decode));
+        if (it != g_winner[is_decode].end() && it->second < n && t[it->second].valid(p)) return it->second;
+    }
+    const int id = heuristic(p, is_decode);
+    return id >= 0 ? id : ATTN_ERR_UNSUPPORTED;
+}
+
+size_t decode_workspace_bytes(int num_seqs, int num_q_heads, int head_dim, int max_kv_len)
+{
+    // sized for the shortest part any instance uses, so every instance fits
+    const int64_t splits = std::max<int64_t>(1, (max_kv_len + kMinSplitLen - 1) / kMinSplitLen);
+    return (size_t)num_seqs * num_q_heads * splits * partial_stride(head_dim) * sizeof(float);
+}
+
+int run(const attn_args *a, int is_decode, hipStream_t stream, int instance_override)
+{
+    int rc = validate(a, is_decode);
+    if (rc != ATTN_OK) return rc;
+    if (a->num_seqs == 0 || a->total_q == 0) return ATTN_OK;
+    KParams p = to_kparams(a, is_decode);
+    if (a->dtype == ATTN_F32) {
+        return launch_prefill_f32(p, stream) == hipSuccess ? ATTN_OK : ATTN_ERR_HIP;
+    }
+    int n;
+    const Instance *t = instances(is_decode, &n);
+    int id = instance_override >= 0 ? instance_override : select_instance(p, a->dtype, is_decode);
+    if (id < 0) return id;
+    if (id >= n || !t[id].valid(p)) return ATTN_ERR_UNSUPPORTED;
+    if (is_decode) {
+        apply_split(p, t[id]);
+        if (p.num_splits > 1) {
+            const size_t need = (size_t)p.num_seqs * p.num_q_heads * p.num_splits * partial_stride(p.head_dim) * sizeof(float);
+            if (!a->workspace || a->workspace_bytes < need) return ATTN_ERR_WORKSPACE;
+        }
+    }
+    if (t[id].launch(p, stream) != hipSuccess) return ATTN_ERR_HIP;
+    if (is_decode && p.num_splits > 1 && launch_decode_combine(p, stream) != hipSuccess) return ATTN_ERR_HIP;
+    return ATTN_OK;
+}
+
+// ---- tuner ----------------------------------------------------------------------------------------
+
+__global__ void fill_bf16_kernel(uint16_t *dst, size_t n, uint32_t seed)
+{
+    // cheap counter hash -> bf16 in roughly [-2, 2); values only need to be finite and varied
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+        uint32_t h = (uint32_t)i * 2654435761u ^ seed;
+        h ^= h >> 15;
+        h *= 2246822519u;
+        h ^= h >> 13;
+        const float f = ((int)(h & 0xffff) - 32768) * (1.f / 16384.f);
+        dst[i] = (uint16_t)(__float_as_uint(f) >> 16);
+    }
+}
+
+struct DeviceBuf {
+    void *p = nullptr;
+    hipError_t alloc(size_t bytes) { return hipMalloc(&p, bytes ? bytes : 16); }
+    ~DeviceBuf()
+    {
+        if (p) (void)hipFree(p);
+    }
+};
+
+int tune(const attn_args *shape, int is_decode, const char *cache_path, int iters, int flags)
+{
+    if (!shape) return ATTN_ERR_NULL;
+    if (shape->struct_bytes != sizeof(attn_args)) return ATTN_ERR_SHAPE;
+    if (shape->dtype != ATTN_BF16) return ATTN_ERR_DTYPE;  // the fp32 path has a single kernel
+    if (shape->num_seqs <= 0 || shape->num_q_heads <= 0 || shape->num_kv_heads <= 0 ||
+        shape->num_q_heads % shape->num_kv_heads || shape->max_kv_len <= 0)
+        return ATTN_ERR_SHAPE;
+    if (shape->head_dim != 64 && shape->head_dim != 128) return ATTN_ERR_UNSUPPORTED;
+    if (iters <= 0) iters = 20;
+    const int B = shape->num_seqs, Hq = shape->num_q_heads, Hkv = shape->num_kv_heads, D = shape->head_dim;
+    const bool paged = is_decode || shape->block_size > 0;
+    const int bs = paged ? (shape->block_size > 0 ? shape->block_size : 16) : 0;
+    if (paged && (bs < 16 || (bs & (bs - 1)))) return ATTN_ERR_UNSUPPORTED;
+    const int max_q = is_decode ? 1 : std::max(1, shape->max_q_len);
+    const int max_kv = std::max(shape->max_kv_len, max_q);
+
+    // synthetic lengths: spread evenly between half of the maximum and the maximum
+    std::vector<int32_t> qsl(B + 1, 0), kvsl(B + 1, 0), lens(B);
+    for (int s = 0; s < B; ++s) {
+        const double f = B > 1 ? 0.5 + 0.5 * (double)((s * 7) % B) / (B - 1) : 1.0;
+        int nq = is_decode ? 1 : std::max(1, (int)(max_q * f));
+        int nkv = std::max(nq, (int)(max_kv * f));
+        if (s == 0) {
+            nq = max_q;
+            nkv = max_kv;
+        }
+        qsl[s + 1] = qsl[s] + nq;
+        kvsl[s + 1] = kvsl[s] + nkv;
+        lens[s] = nkv;
+    }
+    const int total_q = qsl[B];
+    const int64_t total_kv = kvsl[B];
+    int width = 0;
+    int64_t nblocks = 0;
+    std::vector<int32_t> table;
+    if (paged) {
+        width = (max_kv + bs - 1) / bs;
+        for (int s = 0; s < B; ++s) nblocks += (lens[s] + bs - 1) / bs;
+        table.assign((size_t)B * width, -1);
+        // scatter logical blocks over the pool with a stride coprime to its size
+        int64_t stride = 7919;
+        while (std::__gcd(stride, nblocks) != 1) ++stride;
+        int64_t next = 0;
+        for (int s = 0; s < B; ++s)
+            for (int b = 0; b < (lens[s] + bs - 1) / bs; ++b) table[(size_t)s * width + b] = (int32_t)((next++ * stride) % nblocks);
+    }
+
+    const size_t q_elems = (size_t)total_q * Hq * D;
+    const size_t kv_elems = paged ? (size_t)nblocks * bs * Hkv * D : (size_t)total_kv * Hkv * D;
+    DeviceBuf dq, dout, dk, dv, dtab, dqsl, dkvsl, dlens, dws;
+    const size_t ws_bytes = is_decode ? decode_workspace_bytes(B, Hq, D, max_kv) : 0;
+    if (dq.alloc(q_elems * 2) != hipSuccess || dout.alloc(q_elems * 2) != hipSuccess || dk.alloc(kv_elems * 2) != hipSuccess ||
+        dv.alloc(kv_elems * 2) != hipSuccess || dtab.alloc(table.size() * 4) != hipSuccess ||
+        dqsl.alloc((B + 1) * 4) != hipSuccess || dkvsl.alloc((B + 1) * 4) != hipSuccess || dlens.alloc(B * 4) != hipSuccess ||
+        dws.alloc(ws_bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return ATTN_ERR_HIP;
+    }
+    hipLaunchKernelGGL(fill_bf16_kernel, dim3(1024), dim3(256), 0, 0, (uint16_t *)dq.p, q_elems, 1u);
+    hipLaunchKernelGGL(fill_bf16_kernel, dim3(4096), dim3(256), 0, 0, (uint16_t *)dk.p, kv_elems, 2u);
+    hipLaunchKernelGGL(fill_bf16_kernel, dim3(4096), dim3(256), 0, 0, (uint16_t *)dv.p, kv_elems, 3u);
+    bool ok = hipMemcpy(dqsl.p, qsl.data(), (B + 1) * 4, hipMemcpyHostToDevice) == hipSuccess &&
+              hipMemcpy(dkvsl.p, kvsl.data(), (B + 1) * 4, hipMemcpyHostToDevice) == hipSuccess &&
+              hipMemcpy(dlens.p, lens.data(), B * 4, hipMemcpyHostToDevice) == hipSuccess;
+    if (paged && ok) ok = hipMemcpy(dtab.p, table.data(), table.size() * 4, hipMemcpyHostToDevice) == hipSuccess;
+    if (!ok || hipDeviceSynchronize() != hipSuccess) return ATTN_ERR_HIP;
+
+    attn_args a = *shape;
+    a.total_q = total_q;
+    a.max_q_len = max_q;
+    a.max_kv_len = max_kv;
+    a.q = dq.p;
+    a.out = dout.p;
+    a.k = dk.p;
+    a.v = dv.p;
+    a.q_stride_tok = a.o_stride_tok = (int64_t)Hq * D;
+    a.q_stride_head = a.o_stride_head = D;
+    a.kv_stride_head = D;
+    a.kv_stride_tok = (int64_t)Hkv * D;
+    a.kv_stride_block = paged ? (int64_t)bs * Hkv * D : 0;
+    a.block_table = paged ? (const int32_t *)dtab.p : nullptr;
+    a.block_table_stride = width;
+    a.block_size = bs;
+    a.num_blocks = (int32_t)nblocks;
+    a.query_start_loc = (const int32_t *)dqsl.p;
+    a.kv_start_loc = paged ? nullptr : (const int32_t *)dkvsl.p;
+    a.seq_lens = (const int32_t *)dlens.p;
+    if (a.scale == 0.f) a.scale = 1.f / std::sqrt((float)D);
+    a.workspace = dws.p;
+    a.workspace_bytes = ws_bytes;
+
+    int rc = validate(&a, is_decode);
+    if (rc != ATTN_OK) return rc;
+    const KParams p = to_kparams(&a, is_decode);
+    const std::string key = bucket_key(p, a.dtype, is_decode);
+
+    int n;
+    const Instance *t = instances(is_decode, &n);
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return ATTN_ERR_HIP;
+    int best = -1;
+    double best_us = 0;
+    for (int id = 0; id < n; ++id) {
+        if (!t[id].valid(p)) continue;
+        bool fail = false;
+        for (int w = 0; w < 2 && !fail; ++w) fail = run(&a, is_decode, 0, id) != ATTN_OK;
+        if (fail || hipDeviceSynchronize() != hipSuccess) {
+            (void)hipGetLastError();
+            continue;
+        }
+        std::vector<float> ms(iters);
+        for (int i = 0; i < iters && !fail; ++i) {
+            (void)hipEventRecord(e0, 0);
+            fail = run(&a, is_decode, 0, id) != ATTN_OK;
+            (void)hipEventRecord(e1, 0);
+            if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms[i], e0, e1) != hipSuccess) fail = true;
+        }
+        if (fail) continue;
+        std::sort(ms.begin(), ms.end());
+        const double us = 1000.0 * ms[iters / 2];
+        if (flags & 1) fprintf(stderr, "[attn_tune] %s :: %-40s %10.2f us\n", key.c_str(), t[id].name, us);
+        if (best < 0 || us < best_us) {
+            best = id;
+            best_us = us;
+        }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (best < 0) return ATTN_ERR_UNSUPPORTED;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        g_winner[is_decode][key] = best;
+    }
+    if (flags & 1) fprintf(stderr, "[attn_tune] winner %s -> %s (%.2f us)\n", key.c_str(), t[best].name, best_us);
+    if (!cache_path) return ATTN_OK;
+
+    // merge into the file: keep every other line, replace this (environment, bucket) pair
+    std::vector<CacheLine> lines;
+    (void)read_cache_file(cache_path, &lines);  // a missing or damaged file is simply rewritten
+    const std::string env = environment_key();
+    std::vector<CacheLine> keep;
+    for (const CacheLine &cl : lines)
+        if (!(cl.env == env && cl.key == key)) keep.push_back(cl);
+    keep.push_back(CacheLine{env, key, t[best].name, best_us});
+    const std::string tmp = std::string(cache_path) + ".tmp." + std::to_string((long)getpid());
+    {
+        std::ofstream out(tmp, std::ios::trunc);
+        if (!out) return ATTN_ERR_CACHE_IO;
+        out << kCacheMagic << "\n";
+        for (const CacheLine &cl : keep) out << cl.env << "\t" << cl.key << "\t" << cl.inst << "\t" << cl.us << "\n";
+        out.flush();
+        if (!out) {
+            (void)remove(tmp.c_str());
+            return ATTN_ERR_CACHE_IO;
+        }
+    }
+    if (rename(tmp.c_str(), cache_path) != 0) {
+        (void)remove(tmp.c_str());
+        return ATTN_ERR_CACHE_IO;
+    }
+    return ATTN_OK;
+}
+
+}  // namespace
+}  // namespace attn
+
+using namespace attn;
+
+extern "C" {
+
+int attn_prefill_varlen(const attn_args *args, void *hip_stream) { return run(args, 0, (hipStream_t)hip_stream, -1); }
+
+int attn_decode_paged(const attn_args *args, void *hip_stream) { return run(args, 1, (hipStream_t)hip_stream, -1); }
+
+size_t attn_workspace_bytes(const attn_args *a, int is_decode)
+{
+    if (!a || a->struct_bytes != sizeof(attn_args) || !is_decode) return 0;
+    if (a->num_seqs <= 0 || a->num_q_heads <= 0 || a->max_kv_len < 0 || (a->head_dim != 64 && a->head_dim != 128)) return 0;
+    return decode_workspace_bytes(a->num_seqs, a->num_q_heads, a->head_dim, a->max_kv_len);
+}
+
+int attn_tune(const attn_args *shape_like, int is_decode, const char *cache_path, int iters, int flags)
+{
+    return tune(shape_like, is_decode ? 1 : 0, cache_path, iters, flags);
+}
+
+int attn_load_cache(const char *cache_path)
+{
+    if (!cache_path) return ATTN_ERR_NULL;
+    std::lock_guard<std::mutex> lk(g_mu);
+    return load_cache_locked(cache_path);
+}
+
+void attn_clear_cache(void)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_winner[0].clear();
+    g_winner[1].clear();
+}
+
+int attn_num_instances(int is_decode)
+{
+    int n;
+    (void)instances(is_decode ? 1 : 0, &n);
+    return n;
+}
+
+int attn_instance_name(int is_decode, int id, char *buf, size_t buf_bytes)
+{
+    int n;
+    const Instance *t = instances(is_decode ? 1 : 0, &n);
+    if (id < 0 || id >= n) return ATTN_ERR_SHAPE;
+    if (!buf || buf_bytes == 0) return ATTN_ERR_NULL;
+    snprintf(buf, buf_bytes, "%s", t[id].name);
+    return (int)strlen(buf);
+}
+
+int attn_selected_instance(const attn_args *a, int is_decode)
+{
+    is_decode = is_decode ? 1 : 0;
+    if (!a || a->struct_bytes != sizeof(attn_args)) return ATTN_ERR_NULL;
+    if (a->dtype != ATTN_BF16) return ATTN_ERR_DTYPE;
+    if (a->num_q_heads <= 0 || a->num_kv_heads <= 0 || a->num_q_heads % a->num_kv_heads) return ATTN_ERR_SHAPE;
+    const KParams p = to_kparams(a, is_decode);
+    return select_instance(p, a->dtype, is_decode);
+}
+
+void attn_force_instance(int is_decode, int id) { g_forced[is_decode ? 1 : 0].store(id); }
+
+const char *attn_status_string(int status)
+{
+    switch (status) {
+        case ATTN_OK: return "ok";
+        case ATTN_ERR_NULL: return "a required pointer is NULL";
+        case ATTN_ERR_SHAPE: return "inconsistent sizes, strides or head counts";
+        case ATTN_ERR_DTYPE: return "dtype not supported by this entry point";
+        case ATTN_ERR_UNSUPPORTED: return "no kernel instance for this head_dim / block_size / group size";
+        case ATTN_ERR_WORKSPACE: return "workspace missing or too small";
+        case ATTN_ERR_HIP: return "HIP runtime error";
+        case ATTN_ERR_CACHE_IO: return "tuning cache file could not be read or written";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,161 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle, element by element."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2505_03780_amd as A
+import workloads as W
+from attn_testlib import DeviceWorkload, assert_close, check_full, check_sampled, oracle_problem, to_host_f64
+
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+RAGGED = [1, 31, 32, 33, 63, 64, 65, 127, 129, 200, 257]
+
+
+@pytest.fixture(autouse=True)
+def _auto_instance():
+    A.attn_force_instance(False, -1)
+    A.attn_force_instance(True, -1)
+    yield
+    A.attn_force_instance(False, -1)
+    A.attn_force_instance(True, -1)
+
+
+def _valid_instances(dw, is_decode):
+    ids = []
+    a = dw.args(is_decode)
+    for i in range(A.attn_num_instances(is_decode)):
+        A.attn_force_instance(is_decode, i)
+        if A.attn_selected_instance(a, is_decode) == i:
+            ids.append(i)
+    A.attn_force_instance(is_decode, -1)
+    return ids
+
+
+def test_config1_tiny_fp32_full():
+    print("config 1: fp32, L=128, 4 heads, D=64", flush=True)
+    check_full(W.config1())
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_fp32_varlen_gqa_and_paged(D):
+    wl = W.make_prefill_contiguous(11, [1, 5, 64, 65, 130], 4, 2, D, dtype="f32")
+    check_full(wl)
+    wl = W.make_prefill_contiguous(12, [7, 70], 2, 2, D, dtype="f32", causal=False)
+    check_full(wl)
+
+
+@pytest.mark.parametrize("Hq,Hkv,D", [(8, 2, 128), (4, 4, 128), (4, 2, 128), (6, 2, 128), (8, 2, 64), (2, 2, 64)])
+def test_prefill_contiguous_ragged_every_instance(Hq, Hkv, D):
+    wl = W.make_prefill_contiguous(21, RAGGED, Hq, Hkv, D)
+    dw = DeviceWorkload(wl)
+    ref = oracle.attention(oracle_problem(wl))
+    ids = _valid_instances(dw, False)
+    assert ids, "no instance for this shape"
+    for i in ids:
+        print("prefill instance", i, A.attn_instance_name(False, i), "Hq", Hq, "Hkv", Hkv, "D", D, flush=True)
+        A.attn_force_instance(False, i)
+        got = to_host_f64(dw.run(False))
+        assert_close(got, ref, "bf16", A.attn_instance_name(False, i))
+
+
+def test_prefill_non_causal_and_peaked():
+    wl = W.make_prefill_contiguous(22, [50, 129, 300], 8, 2, 128, causal=False)
+    check_full(wl)
+    # peaked softmax (scores ~ N(0, 36)): max-abs becomes a meaningful bound
+    wl = W.make_prefill_contiguous(23, [200, 333], 8, 2, 128, scale=6.0 / np.sqrt(128.0))
+    check_full(wl)
+
+
+def test_prefill_with_empty_sequences_in_batch():
+    wl = W.make_prefill_contiguous(24, [0, 70, 0, 5, 0], 8, 2, 128)
+    check_full(wl)
+
+
+def _chunked(seed, q_lens, kv_lens, Hq=8, Hkv=2, D=128, bs=16, nb=None):
+    nb = nb or int(sum((n + bs - 1) // bs for n in kv_lens)) + 5
+    return W.make_paged(seed, "prefill", q_lens, kv_lens, Hq, Hkv, D, bs, nb)
+
+
+def test_chunked_prefill_over_paged_prefix_every_instance():
+    wl = _chunked(31, [64, 1, 33, 100, 17, 128], [64, 90, 33, 500, 270, 1000])
+    dw = DeviceWorkload(wl)
+    ref = oracle.attention(oracle_problem(wl))
+    for i in _valid_instances(dw, False):
+        print("chunked prefill instance", i, A.attn_instance_name(False, i), flush=True)
+        A.attn_force_instance(False, i)
+        assert_close(to_host_f64(dw.run(False)), ref, "bf16", A.attn_instance_name(False, i))
+
+
+@pytest.mark.parametrize("bs", [16, 32, 128])
+def test_paged_block_sizes(bs):
+    wl = _chunked(32, [40, 70], [100, 333], bs=bs)
+    check_full(wl)
+    wl = W.make_paged(33, "decode", [1, 1, 1], [1, 77, 600], 8, 2, 128, bs, 64)
+    check_full(wl)
+
+
+DECODE_LENS = [1, 15, 16, 17, 31, 32, 33, 100, 255, 256, 257, 700, 1500]
+
+
+@pytest.mark.parametrize("Hq,Hkv,D", [(32, 8, 128), (16, 2, 128), (4, 4, 128), (8, 2, 64)])
+def test_decode_every_instance(Hq, Hkv, D):
+    wl = W.make_paged(41, "decode", np.ones(len(DECODE_LENS), np.int32), DECODE_LENS, Hq, Hkv, D, 16, 400)
+    dw = DeviceWorkload(wl)
+    ref = oracle.attention(oracle_problem(wl))
+    ids = _valid_instances(dw, True)
+    assert ids
+    for i in ids:
+        print("decode instance", i, A.attn_instance_name(True, i), "Hq", Hq, "Hkv", Hkv, "D", D, flush=True)
+        A.attn_force_instance(True, i)
+        assert_close(to_host_f64(dw.run(True)), ref, "bf16", A.attn_instance_name(True, i))
+
+
+def test_decode_peaked_and_one_short_sequence_with_many_splits():
+    lens = [1] + [3000] * 3
+    wl = W.make_paged(42, "decode", np.ones(4, np.int32), lens, 32, 8, 128, 16, 600, scale=5.0 / np.sqrt(128.0))
+    dw = DeviceWorkload(wl)
+    ref = oracle.attention(oracle_problem(wl))
+    for i in _valid_instances(dw, True):
+        A.attn_force_instance(True, i)
+        assert_close(to_host_f64(dw.run(True)), ref, "bf16", A.attn_instance_name(True, i))
+
+
+# ---- the benchmark configurations at full size ------------------------------------------------
+
+def test_config2_decode_8b_full_size():
+    print("config 2: paged decode, batch 64, ctx U[512,4096]", flush=True)
+    check_full(W.config2())
+
+
+def test_config3_prefill_8b_full_size_sampled():
+    print("config 3: varlen prefill, 8 sequences U[256,2048]", flush=True)
+    wl = W.config3()
+    check_sampled(wl, 1500, seed=3)
+    # and one whole short sequence, every row (sequence 1: 409 tokens)
+    dw = DeviceWorkload(wl)
+    out = to_host_f64(dw.run(False))
+    s = 1
+    seqs = np.repeat(s, 409 * 4)
+    toks = np.tile(np.arange(409), 4)
+    heads = np.repeat([0, 7, 18, 31], 409)
+    ref = oracle.attention_rows(oracle_problem(wl), seqs, toks, heads)
+    got = out[wl.query_start_loc[s] + toks, heads]
+    assert_close(got, ref, "bf16", "config 3 sequence 1")
+
+
+def test_config4_chunked_prefill_full_size_sampled():
+    print("config 4: chunked prefill over paged prefix", flush=True)
+    check_sampled(W.config4(), 600, seed=4)
+
+
+def test_config5_decode_70b_long_full_size():
+    print("config 5: long-context paged decode, split-K", flush=True)
+    wl = W.config5()
+    dw = DeviceWorkload(wl)
+    a = dw.args(True)
+    name = A.attn_instance_name(True, A.attn_selected_instance(a, True))
+    assert "split0" not in name, "long contexts must take the split-K path, got " + name
+    check_sampled(wl, 16 * 64, seed=5, dw=dw)

@@ -1,0 +1,167 @@
+"""Host-side logic of the library, exercised without a GPU: exports, validation, buckets, cache."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2505_03780_amd as A
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _args(**kw):
+    a = A.AttnArgs()
+    a.struct_bytes = ctypes.sizeof(A.AttnArgs)
+    a.dtype = A.ATTN_BF16
+    a.num_seqs, a.num_q_heads, a.num_kv_heads, a.head_dim = 4, 32, 8, 128
+    a.total_q, a.max_q_len, a.max_kv_len = 400, 100, 100
+    a.q = a.out = a.k = a.v = 0x1000
+    a.q_stride_tok = a.o_stride_tok = 32 * 128
+    a.q_stride_head = a.o_stride_head = 128
+    a.kv_stride_tok, a.kv_stride_head, a.kv_stride_block = 8 * 128, 128, 16 * 8 * 128
+    a.query_start_loc = a.seq_lens = 0x2000
+    a.scale, a.causal = 0.088, 1
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return a
+
+
+def _paged(**kw):
+    base = dict(block_table=0x3000, block_table_stride=64, block_size=16, num_blocks=1024)
+    base.update(kw)
+    return _args(**base)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "attn.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(attn_[a-z_]+)\s*\(", header))
+    assert {"attn_prefill_varlen", "attn_decode_paged", "attn_tune", "attn_workspace_bytes"} <= names
+    lib = A.load_library()
+    for n in sorted(names):
+        assert hasattr(lib, n), "missing export " + n
+
+
+def test_struct_layout_matches_and_workspace_bytes():
+    a = _paged(total_q=4, max_q_len=1, max_kv_len=4096)
+    # 4 seqs * 32 heads * ceil(4096/256) parts * (128 + 2) floats
+    assert A.attn_workspace_bytes(a, True) == 4 * 32 * 16 * 130 * 4
+    assert A.attn_workspace_bytes(a, False) == 0
+    a.struct_bytes += 8
+    assert A.attn_workspace_bytes(a, True) == 0
+
+
+def test_status_strings():
+    assert A.attn_status_string(0) == "ok"
+    for code in range(-7, 0):
+        assert A.attn_status_string(code) not in ("ok", "unknown status")
+    assert A.attn_status_string(-99) == "unknown status"
+
+
+@pytest.mark.parametrize("mutate,decode,code", [
+    (dict(struct_bytes=8), False, -2),
+    (dict(dtype=7), False, -3),
+    (dict(dtype=A.ATTN_F32), True, -3),
+    (dict(num_kv_heads=5), False, -2),
+    (dict(head_dim=96), False, -4),
+    (dict(q=None), False, -1),
+    (dict(seq_lens=None), False, -1),
+    (dict(query_start_loc=None), False, -1),
+    (dict(q_stride_tok=32 * 128 + 4), False, -2),
+    (dict(q=0x1008), False, -2),
+    (dict(q_stride_head=64), False, -2),
+])
+def test_validation_errors_without_touching_the_device(mutate, decode, code):
+    lib = A.load_library()
+    a = _args(**mutate)
+    fn = lib.attn_decode_paged if decode else lib.attn_prefill_varlen
+    assert fn(a, None) == code
+
+
+def test_validation_of_paged_arguments():
+    lib = A.load_library()
+    assert lib.attn_decode_paged(_args(total_q=4, max_q_len=1), None) == -1  # decode needs a block table
+    assert lib.attn_decode_paged(_paged(total_q=5, max_q_len=1), None) == -2  # one token per sequence
+    assert lib.attn_prefill_varlen(_paged(block_size=24), None) == -4
+    assert lib.attn_prefill_varlen(_paged(block_size=8), None) == -4
+    assert lib.attn_prefill_varlen(_paged(max_kv_len=64 * 16 + 1), None) == -2  # table too narrow
+    assert lib.attn_prefill_varlen(None, None) == -1
+    # empty batches are fine and enqueue nothing
+    assert lib.attn_prefill_varlen(_args(num_seqs=0, total_q=0, q=None, out=None), None) == 0
+
+
+def test_instance_tables_and_heuristic_selection():
+    names_p = [A.attn_instance_name(False, i) for i in range(A.attn_num_instances(False))]
+    names_d = [A.attn_instance_name(True, i) for i in range(A.attn_num_instances(True))]
+    assert len(set(names_p)) == len(names_p) and len(set(names_d)) == len(names_d)
+    with pytest.raises(A.AttnError):
+        A.attn_instance_name(False, len(names_p))
+    A.attn_clear_cache()
+    A.attn_force_instance(False, -1)
+    A.attn_force_instance(True, -1)
+    # GQA 32/8 prefill packs the 4 heads of a KV head into one workgroup
+    i = A.attn_selected_instance(_args(), False)
+    assert "hpw4" in names_p[i] and "d128" in names_p[i]
+    # MHA cannot
+    i = A.attn_selected_instance(_args(num_kv_heads=32), False)
+    assert "hpw1" in names_p[i]
+    # head_dim 64 picks a d64 instance
+    i = A.attn_selected_instance(_args(head_dim=64), False)
+    assert "d64" in names_p[i]
+    # long-context decode with few sequences takes split-K; short contexts do not split
+    long = _paged(num_seqs=16, total_q=16, max_q_len=1, max_kv_len=32768, block_table_stride=2048, num_q_heads=64)
+    assert "split0" not in names_d[A.attn_selected_instance(long, True)]
+    short = _paged(num_seqs=512, total_q=512, max_q_len=1, max_kv_len=200)
+    assert "split0" in names_d[A.attn_selected_instance(short, True)]
+    # a forced instance that does not fit the shape is refused, not silently replaced
+    d64 = next(i for i, n in enumerate(names_p) if "d64" in n)
+    A.attn_force_instance(False, d64)
+    assert A.attn_selected_instance(_args(), False) == -4
+    A.attn_force_instance(False, -1)
+
+
+def test_cache_file_round_trip_stale_and_corrupt(tmp_path):
+    names_p = [A.attn_instance_name(False, i) for i in range(A.attn_num_instances(False))]
+    A.attn_clear_cache()
+    default = A.attn_selected_instance(_args(), False)
+    other = next(i for i, n in enumerate(names_p) if "d128" in n and "hpw1" in n and i != default)
+    key = "prefill|bf16|d128|hq32|hkv8|contig|bs0|c1|B2|q7|kv7"
+    env_here = "nodevice|cu0|k1"  # what the library reports in a process without a GPU
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("environment key differs on a GPU box; covered by the GPU tuner test")
+    good = tmp_path / "cache.txt"
+    good.write_text("attn-tune-cache-v1\n%s\t%s\t%s\t12.5\n" % (env_here, key, names_p[other]))
+    assert A.attn_load_cache(str(good)) == 0
+    assert A.attn_selected_instance(_args(), False) == other
+    # another bucket is untouched
+    assert A.attn_selected_instance(_args(max_kv_len=5000, max_q_len=5000), False) == default
+    A.attn_clear_cache()
+    assert A.attn_selected_instance(_args(), False) == default
+    # stale environment (another device / build): entry ignored
+    stale = tmp_path / "stale.txt"
+    stale.write_text("attn-tune-cache-v1\ngfx942|cu304|hip0|k0\t%s\t%s\t12.5\n" % (key, names_p[other]))
+    assert A.attn_load_cache(str(stale)) == 0
+    assert A.attn_selected_instance(_args(), False) == default
+    # unknown instance name: ignored
+    unk = tmp_path / "unk.txt"
+    unk.write_text("attn-tune-cache-v1\n%s\t%s\tno such kernel\t1\n" % (env_here, key))
+    assert A.attn_load_cache(str(unk)) == 0
+    assert A.attn_selected_instance(_args(), False) == default
+    # corrupt and missing files report an error and change nothing
+    bad = tmp_path / "bad.txt"
+    bad.write_text("garbage\n")
+    assert A.attn_load_cache(str(bad)) == -7
+    bad.write_text("attn-tune-cache-v1\nonly\ttwo\n")
+    assert A.attn_load_cache(str(bad)) == -7
+    assert A.attn_load_cache(str(tmp_path / "missing.txt")) == -7
+    assert A.attn_selected_instance(_args(), False) == default
+
+
+def test_tune_rejects_bad_requests_before_touching_the_device():
+    lib = A.load_library()
+    assert lib.attn_tune(None, 0, None, 1, 0) == -1
+    assert lib.attn_tune(_args(dtype=A.ATTN_F32), 0, None, 1, 0) == -3
+    assert lib.attn_tune(_args(head_dim=80), 0, None, 1, 0) == -4
+    assert lib.attn_tune(_args(num_kv_heads=5), 0, None, 1, 0) == -2
