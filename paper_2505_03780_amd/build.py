@@ -15,15 +15,20 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libattn_gfx950.so")
-SOURCES = ["attn_api.hip", "prefill_f32.hip", "prefill_bf16.hip", "decode_bf16.hip"]
+SOURCES = ["attn_api.hip", "prefill_f32.hip", "prefill_bf16.hip", "prefill_bf16_ring.hip", "decode_bf16.hip"]
 # Packed fp32 instructions are switched off on purpose (see DESIGN notes in the repository root).
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
+# The MFMA kernels never do arithmetic on NaN (garbage rows are replaced by selects before any use),
+# so the compiler may skip the canonicalising v_max it otherwise puts in front of every fmaxf.
+EXTRA = {"prefill_bf16_ring.hip": ["-fno-honor-nans"]}
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(BUILD, src.replace(".hip", ".o"))
-    cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = ["hipcc", *FLAGS, *EXTRA.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed for %s:\n%s" % (src, r.stderr[-4000:]))

@@ -177,7 +177,8 @@ int heuristic(const KParams &p, int is_decode)
     if (!is_decode) {
         // pack as many heads of a KV head as divide the group: they share every K/V tile
         int hpw = p.group % 4 == 0 ? 4 : (p.group % 2 == 0 ? 2 : 1);
-        id = find_instance(0, p, 4, hpw, 64, 64 * 4, 0);
+        id = find_instance(0, p, 4, hpw, 32, 64 * 4, 0);                // LDS-ring kernel (D = 128)
+        if (id < 0) id = find_instance(0, p, 4, hpw, 64, 64 * 4, 0);  // register-staged kernel
     } else {
         // enough workgroups to fill 256 CUs several times over, but parts no shorter than 256 keys
         const int64_t units = (int64_t)p.num_seqs * p.num_kv_heads;
@@ -521,6 +522,22 @@ int tune(const attn_args *shape, int is_decode, const char *cache_path, int iter
 }
 
 }  // namespace
+
+const Instance *prefill_instances(int *count)
+{
+    static const std::vector<Instance> all = [] {
+        std::vector<Instance> v;
+        int n;
+        const Instance *t = prefill_ring_instances(&n);
+        v.insert(v.end(), t, t + n);
+        t = prefill_staged_instances(&n);
+        v.insert(v.end(), t, t + n);
+        return v;
+    }();
+    *count = (int)all.size();
+    return all.data();
+}
+
 }  // namespace attn
 
 using namespace attn;

@@ -53,7 +53,9 @@ struct Instance {
     hipError_t (*launch)(const KParams &, hipStream_t);
 };
 
-const Instance *prefill_instances(int *count);
+const Instance *prefill_instances(int *count);         // all prefill instances, ring variants first
+const Instance *prefill_ring_instances(int *count);    // LDS-ring, software-pipelined (D = 128)
+const Instance *prefill_staged_instances(int *count);  // register-staged double buffer (D = 64, 128)
 const Instance *decode_instances(int *count);
 
 hipError_t launch_prefill_f32(const KParams &, hipStream_t);

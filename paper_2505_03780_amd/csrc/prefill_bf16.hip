@@ -321,7 +321,7 @@ hipError_t prefill_launch(const KParams &p, hipStream_t stream)
 
 }  // namespace
 
-const Instance *prefill_instances(int *count)
+const Instance *prefill_staged_instances(int *count)
 {
     // Built inside a host function so that the table of host function pointers is not
     // emitted for the device.

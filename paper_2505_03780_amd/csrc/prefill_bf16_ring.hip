@@ -1,0 +1,615 @@
+// Causal variable-length prefill on bf16 MFMA (gfx950): LDS-ring, software-pipelined variant.
+//
+// Same operation and same operand layout as prefill_bf16.hip (tiled online-softmax
+// attention, the FlashAttention-2 formulation of the paper's kernel, section
+// "Method and Investigated Kernels"; causal, variable-length, grouped-query heads),
+// restructured so that the matrix cores and the vector ALU work at the same time:
+//
+//  * K and V travel HBM -> LDS with global_load_lds (no registers, no ds_write) into a
+//    ring of NSLOT slots of 32 keys; PF units are in flight, counted with s_waitcnt
+//    vmcnt, one workgroup barrier per 32-key unit.  The 16-byte chunks of a row are
+//    XOR-swizzled (by choosing which global chunk each lane fetches) so that both the
+//    128-bit K reads and the transposing 64-bit V reads are free of bank conflicts
+//    without padding.
+//  * The unit loop is software pipelined: while the MFMAs of S(u+1) = K(u+1) Q^T run,
+//    the ALU exponentiates S(u); while the MFMAs of O += V(u) P(u) run, it takes the
+//    row maxima of S(u+1) and applies the masks.
+//  * The running maximum is only moved when it would grow by more than 2^kSlack
+//    (then O and l are rescaled); otherwise exponentials are taken against the stale
+//    reference.  The result is unchanged, because numerator and denominator
+//    carry the same reference, and the rescale of the accumulators becomes rare.
+//  * The output tile is transposed through LDS and written as whole 256-byte rows.
+#include "kernel_params.hpp"
+
+namespace attn {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void gbl_void;
+
+constexpr int kHD = 128;
+constexpr int kUnit = 32;          // keys per pipeline unit
+constexpr int kSlotBytes = 16384;  // 32 K rows + 32 V rows of 256 bytes
+constexpr int kVOff = 8192;
+constexpr float kSlack = 8.f;      // log2 of the largest weight tolerated before the reference moves
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// value of the same register in lane ^ 32
+__device__ __forceinline__ float swap32_max(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float swap32_sum(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// s_waitcnt with only vmcnt constrained (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+}
+
+// chunk swizzle of a row inside a unit: rows r..r+15 get 16 distinct values (128-bit K reads),
+// rows r..r+3 differ in the upper two bits (64-bit transposing V reads)
+__device__ __forceinline__ int swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+
+template <int QB, int HPW, int NSLOT, int PF>
+struct RingCfg {
+    static constexpr int kWaves = 4;
+    static constexpr int kTSub = kWaves / HPW;
+    static constexpr int kWaveTok = 32 * QB;
+    static constexpr int kTok = kTSub * kWaveTok;
+    static constexpr int kThreads = 256;
+    static constexpr size_t kLdsBytes = (size_t)NSLOT * kSlotBytes;
+    static_assert(NSLOT >= PF + 2, "ring too small for the prefetch distance");
+    static_assert(PF >= 3, "K of unit u+2 is read one iteration ahead, so three units must be resident");
+    static_assert(kWaves % HPW == 0, "waves must split evenly over heads");
+    static_assert(kLdsBytes >= (size_t)kWaves * kWaveTok * kHD * 2, "epilogue staging must fit in the ring");
+};
+
+template <int QB, int HPW, int NSLOT, int PF, bool PAGED>
+__global__ __launch_bounds__(256) void prefill_ring_kernel(const KParams p)
+{
+    using C = RingCfg<QB, HPW, NSLOT, PF>;
+    constexpr int KSTEPS = kHD / 16;
+    constexpr int DB = kHD / 32;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+
+    // ---- which (head group, sequence, query tile) ---------------------------------------------
+    const int groups_per_kvh = p.group / HPW;
+    const int nhg = p.num_kv_heads * groups_per_kvh;
+    int bid = blockIdx.x;
+    const int hg = bid % nhg;
+    bid /= nhg;
+    const int s = bid % p.num_seqs;
+    const int r = bid / p.num_seqs;
+    const int kvh = hg % p.num_kv_heads;
+    const int hsub = hg / p.num_kv_heads;
+
+    const int q0 = p.query_start_loc[s];
+    const int n_q = p.query_start_loc[s + 1] - q0;
+    const int n_kv = p.seq_lens[s];
+    const int off = n_kv - n_q;
+    const int n_tiles_q = (n_q + C::kTok - 1) / C::kTok;
+    const int qtile = n_tiles_q - 1 - r;
+    if (qtile < 0) return;
+    const int t0 = qtile * C::kTok;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lhalf = lane >> 5;
+    const int l32 = lane & 31;
+    const int l16 = lane & 15;
+    const int head = kvh * p.group + hsub * HPW + (wave % HPW);
+    const int t0w = t0 + (wave / HPW) * C::kWaveTok;
+
+    // scores are exponentiated as 2^(c*s - ref); a negative scale is moved into Q (sign flips are exact)
+    const float c = fabsf(p.scale_log2e);
+    const bool negate_q = p.scale_log2e < 0.f;
+
+    // ---- Q fragments ---------------------------------------------------------------------------
+    const __bf16 *qbase = (const __bf16 *)p.q;
+    bf16x8 qf[QB][KSTEPS];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        int t = t0w + qb * 32 + l32;
+        t = t < n_q ? t : n_q - 1;
+        const __bf16 *src = qbase + (int64_t)(q0 + t) * p.q_stride_tok + (int64_t)head * p.q_stride_head + 8 * lhalf;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            u32x4 raw = *(const u32x4 *)(src + 16 * ks);
+            if (negate_q) raw ^= 0x80008000u;
+            qf[qb][ks] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+
+    // ---- key range -------------------------------------------------------------------------------
+    int kv_end = n_kv;
+    if (p.causal) {
+        const int last_tok = t0 + C::kTok < n_q ? t0 + C::kTok : n_q;
+        kv_end = off + last_tok < n_kv ? off + last_tok : n_kv;
+    }
+    const int n_units = (kv_end + kUnit - 1) / kUnit;
+
+    __bf16 *obase = (__bf16 *)p.out;
+    if (n_units == 0) {  // no visible key at all (non-causal call on an empty context): zeros
+        for (int i = lane; i < C::kWaveTok * (kHD / 8); i += 64) {
+            const int t = t0w + i / (kHD / 8);
+            if (t < n_q)
+                *(u32x4 *)(obase + (int64_t)(q0 + t) * p.o_stride_tok + (int64_t)head * p.o_stride_head + 8 * (i % (kHD / 8))) =
+                    u32x4{0u, 0u, 0u, 0u};
+        }
+        return;
+    }
+
+    // first key position of this wave's rows, and the first unit that needs masking for this wave
+    const int qpos_lo = p.causal ? off + t0w : 0x7fffff00;
+    int first_masked = (qpos_lo + 1) / kUnit;             // units below lie entirely at or before qpos_lo
+    first_masked = first_masked < n_kv / kUnit ? first_masked : n_kv / kUnit;  // and entirely inside the sequence
+    int qrel[QB];  // key index (relative to the lane's first key of a unit) up to which a row sees keys
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const int qp = p.causal ? off + t0w + qb * 32 + l32 : 0x7fffff00;
+        const int lim = qp < n_kv - 1 ? qp : n_kv - 1;  // last visible key
+        qrel[qb] = lim - 4 * lhalf;
+    }
+
+    // ---- DMA of one unit: wave w moves rows 8w..8w+7 of K and of V (2 x 1 KB each) -------------
+    // The address of a transfer is a wave-uniform 64-bit base (SGPRs: pool block or packed row of the
+    // unit, KV head) plus a 32-bit per-lane offset (row inside the block, swizzled 16-byte chunk).
+    // The eight rows of a wave never straddle a 16-key block, so the table entry is wave-uniform.
+    const unsigned char *kbase = (const unsigned char *)p.k + (int64_t)kvh * p.kv_stride_head * 2;
+    const unsigned char *vbase = (const unsigned char *)p.v + (int64_t)kvh * p.kv_stride_head * 2;
+    const int kv0 = PAGED ? 0 : p.kv_start_loc[s];
+    const int32_t *bt_row = PAGED ? p.block_table + (int64_t)s * p.block_table_stride : nullptr;
+    const int dma_row = 8 * wave + (lane >> 4);  // + 4*i, row inside the unit
+    const uint32_t tok_bytes = (uint32_t)p.kv_stride_tok * 2;
+    const int last_unit0 = (n_kv - 1) & ~(kUnit - 1);  // first key of the last unit that holds a real key
+    uint32_t dma_chunk_off[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) dma_chunk_off[i] = 16 * ((lane & 15) ^ swz(dma_row + 4 * i));
+    // wave-uniform table entry of the block that holds this wave's rows of `unit` (clamped to the sequence)
+    auto table_entry = [&](int unit) -> int {
+        if (!PAGED) return 0;
+        int u0 = unit * kUnit < last_unit0 ? unit * kUnit : last_unit0;
+        int row = u0 + 8 * wave;
+        row = row < n_kv ? row : n_kv - 1;
+        return __builtin_amdgcn_readfirstlane(bt_row[row >> p.block_shift]);
+    };
+    auto issue_unit = [&](int unit, int entry) {
+        unsigned char *slot = lds + (unit % NSLOT) * kSlotBytes + 8 * wave * 256;
+        const int u0 = unit * kUnit < last_unit0 ? unit * kUnit : last_unit0;  // units past the end repeat the last one
+        // uniform part
+        int64_t base;
+        int first_row;  // key index that a per-lane row offset of 0 stands for
+        if (PAGED) {
+            int wrow = u0 + 8 * wave;
+            wrow = wrow < n_kv ? wrow : n_kv - 1;
+            first_row = wrow & ~(p.block_size - 1);
+            base = (int64_t)entry * p.kv_stride_block * 2;
+        } else {
+            first_row = u0;
+            base = (int64_t)(kv0 + u0) * tok_bytes;
+        }
+        const unsigned char *kb = kbase + base, *vb = vbase + base;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            int row = u0 + dma_row + 4 * i;
+            row = row < n_kv ? row : n_kv - 1;  // rows past the end re-read the last key (finite, masked)
+            const uint32_t o = (uint32_t)(row - first_row) * tok_bytes + dma_chunk_off[i];
+            __builtin_amdgcn_global_load_lds((gbl_void *)(kb + o), (lds_void *)(slot + 4 * i * 256), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gbl_void *)(vb + o), (lds_void *)(slot + kVOff + 4 * i * 256), 16, 0, 0);
+        }
+    };
+
+    // Publish the ring.  Each wave issues 4 transfers per unit and memory operations complete in order,
+    // so once at most 4*(PF-3) are outstanding, this wave's transfers of every unit but the newest PF-3
+    // have landed (a table load that sits between them only makes the wait stricter).  All LDS reads of
+    // the slot about to be refilled have returned, because their values fed MFMAs issued earlier.  A
+    // bare s_barrier is used: the fence of __syncthreads would drain vmcnt to zero and with it the
+    // whole prefetch queue.
+    auto ring_barrier = [&]() {
+        wait_vmcnt<4 * (PF - 3)>();
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // ---- per-lane LDS read offsets ----------------------------------------------------------------
+    int koff[KSTEPS];
+    {
+        const int kx = swz(l32);
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) koff[ks] = l32 * 256 + 16 * ((2 * ks + lhalf) ^ kx);
+    }
+    int voff[DB][2];
+    {
+        const int a = l16 >> 2, h1 = (lane >> 4) & 1, h0 = (lane & 3) >> 1;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int rd = 0; rd < 2; ++rd)
+                voff[db][rd] = kVOff + (8 * rd + 4 * lhalf + a) * 256 +
+                               16 * (((db ^ a) << 2) | (2 * (h1 ^ rd)) | (h0 ^ lhalf)) + 8 * (lane & 1);
+    }
+
+    // ---- state ---------------------------------------------------------------------------------------
+    f32x16 oacc[QB][DB];
+    f32x16 s_cur[QB], s_nxt[QB];
+    float m_ref[QB], l_run[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        m_ref[qb] = -INFINITY;
+        l_run[qb] = 0.f;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) oacc[qb][db][v] = 0.f;
+    }
+
+    // S(u) = K(u) Q^T for both query blocks
+    auto qk = [&](int unit, f32x16 (&sacc)[QB]) {
+        const unsigned char *kt = lds + (unit % NSLOT) * kSlotBytes;
+        bf16x8 kf[KSTEPS];
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) kf[ks] = *(const bf16x8 *)(kt + koff[ks]);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sacc[qb][v] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[qb][ks], sacc[qb], 0, 0, 0);
+        }
+    };
+    // O^T += V(u)^T P^T
+    auto pv = [&](int unit, const bf16x8 (&pf)[QB][2]) {
+        const unsigned char *vt = lds + (unit % NSLOT) * kSlotBytes;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vt + voff[db][0] + ks * 16 * 256));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vt + voff[db][1] + ks * 16 * 256));
+                const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][ks], oacc[qb][db], 0, 0, 0);
+            }
+        }
+    };
+    // Move the reference of the rows whose new maximum outgrew it by more than the slack; rare, and
+    // wave-uniform, so the accumulators are only touched when needed.
+    auto move_reference = [&](const float (&bm)[QB]) {
+        bool grow = false;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) grow |= bm[qb] > m_ref[qb] + kSlack;
+        if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                float m_new = fmaxf(m_ref[qb], bm[qb]);
+                m_new = m_new == -INFINITY ? 0.f : m_new;
+                const float alpha = fast_exp2(m_ref[qb] - m_new);
+                m_ref[qb] = m_new;
+                l_run[qb] *= alpha;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) oacc[qb][db][v] *= alpha;
+            }
+        }
+    };
+    // Row maxima of a fresh score tile (masked if MASK), then move the reference if a row outgrew it.
+    // With MASK the tile is left scaled (x = c*s, masked entries -inf); without, it stays raw.
+    auto settle = [&](int unit, f32x16 (&sacc)[QB], auto mask_tag) {
+        constexpr bool MASK = decltype(mask_tag)::value;
+        float bm[QB];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            if (MASK) {
+                const int rel = qrel[qb] - unit * kUnit;  // entries with 8*(v/4) + (v%4) > rel are hidden
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float x = sacc[qb][v] * c;
+                    sacc[qb][v] = (8 * (v >> 2) + (v & 3)) > rel ? -INFINITY : x;
+                }
+            }
+            float mx = fmaxf(fmaxf(sacc[qb][0], sacc[qb][1]), sacc[qb][2]);
+#pragma unroll
+            for (int v = 3; v < 15; v += 2) mx = fmaxf(fmaxf(mx, sacc[qb][v]), sacc[qb][v + 1]);
+            mx = fmaxf(mx, sacc[qb][15]);
+            mx = swap32_max(mx);
+            bm[qb] = MASK ? mx : mx * c;
+        }
+        move_reference(bm);
+    };
+    // P = 2^(x - ref) as bf16 B operands; row sums are taken over the rounded values
+    auto exponentiate = [&](const f32x16 (&sacc)[QB], bf16x8 (&pf)[QB][2], auto mask_tag) {
+        constexpr bool MASK = decltype(mask_tag)::value;
+        bf16x2 ones;
+        ones[0] = (__bf16)1.f;
+        ones[1] = (__bf16)1.f;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            float sum = 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; v += 2) {
+                const float e0 = fast_exp2(MASK ? sacc[qb][v] - m_ref[qb] : __builtin_fmaf(sacc[qb][v], c, -m_ref[qb]));
+                const float e1 = fast_exp2(MASK ? sacc[qb][v + 1] - m_ref[qb] : __builtin_fmaf(sacc[qb][v + 1], c, -m_ref[qb]));
+                bf16x2 pr;
+                pr[0] = (__bf16)e0;
+                pr[1] = (__bf16)e1;
+                sum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, sum, false);
+                pf[qb][v >> 3][v & 7] = pr[0];
+                pf[qb][v >> 3][(v & 7) + 1] = pr[1];
+            }
+            l_run[qb] += sum;
+        }
+    };
+
+    // ---- prologue: PF units in flight, S(0) ready ------------------------------------------------
+#pragma unroll
+    for (int u = 0; u < PF; ++u) issue_unit(u, table_entry(u));
+    ring_barrier();
+    qk(0, s_cur);
+    using Masked = std::integral_constant<bool, true>;
+    using Plain = std::integral_constant<bool, false>;
+    bool cur_masked = first_masked <= 0;
+    if (cur_masked)
+        settle(0, s_cur, Masked{});
+    else
+        settle(0, s_cur, Plain{});
+    bf16x8 kf[KSTEPS];  // K fragments of the next unit, fetched one iteration ahead
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) kf[ks] = *(const bf16x8 *)(lds + (1 % NSLOT) * kSlotBytes + koff[ks]);
+
+    // ---- main loop ------------------------------------------------------------------------------------
+    // Invariant at the top of iteration u: S(u) settled in `cur`; units u and u+1 resident; units up to
+    // u+PF-1 issued.  S(u+1) is always computed, also past the last unit (the ring slot then holds
+    // the clamped rows of a dummy transfer): that keeps every iteration one straight-line block.
+    // One iteration is written as groups of "one MFMA plus the vector and LDS work that hides under
+    // it", fenced by scheduling barriers, because a wavefront issues in order: the matrix pipe only
+    // stays busy if independent ALU work sits between consecutive MFMAs in program order.
+    //   phase X: S(u+1) += K(u+1) Q^T, one MFMA per group, with the exponentials of one pair of
+    //            scores of S(u) and one or two transposing V(u) reads per group;
+    //   phase Y: O += V(u) P(u), one MFMA per group, with the row maxima (and masks) of S(u+1), the
+    //            K(u+2) fragment reads for the next iteration and the transfers of unit u+PF.
+    // Invariant at the top of iteration u: S(u) settled in `cur`; kf = K(u+1); units <= u+2 resident;
+    // units <= u+PF-1 issued.  S(u+1) is computed even past the last unit (its ring slot then holds the
+    // re-read rows of a dummy transfer and every entry is masked): no branch inside the iteration.
+#ifdef ATTN_RING_PROFILE
+    unsigned long long prof_t[5] = {0, 0, 0, 0, 0}, prof_last = __builtin_readcyclecounter();
+#define PROF_MARK(i)                                                   \
+    {                                                                  \
+        const unsigned long long now = __builtin_readcyclecounter();   \
+        prof_t[i] += now - prof_last;                                  \
+        prof_last = now;                                               \
+    }
+#else
+#define PROF_MARK(i)
+#endif
+    auto iteration = [&](int u, f32x16 (&cur)[QB], f32x16 (&nxt)[QB], auto cur_tag, auto nxt_tag) {
+        constexpr bool CUR_MASK = decltype(cur_tag)::value;
+        constexpr bool NXT_MASK = decltype(nxt_tag)::value;
+        constexpr int G = 8 * QB;  // MFMAs per product
+        const unsigned char *vt = lds + (u % NSLOT) * kSlotBytes;
+        const unsigned char *kt2 = lds + ((u + 2) % NSLOT) * kSlotBytes;
+        const int entry = table_entry(u + PF);  // scalar load, consumed at the end of phase Y
+
+        bf16x8 pf[QB][2];
+        s16x4 vraw[2 * DB][2];
+        float sum[QB];
+        bf16x2 ones;
+        ones[0] = (__bf16)1.f;
+        ones[1] = (__bf16)1.f;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) sum[qb] = 0.f;
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const int ks = g / QB, qb = g % QB;
+            nxt[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[qb][ks], ks == 0 ? zero : nxt[qb], 0, 0, 0);
+            {
+                const int v = 2 * (g / QB);
+                const float e0 = fast_exp2(CUR_MASK ? cur[qb][v] - m_ref[qb] : __builtin_fmaf(cur[qb][v], c, -m_ref[qb]));
+                const float e1 = fast_exp2(CUR_MASK ? cur[qb][v + 1] - m_ref[qb] : __builtin_fmaf(cur[qb][v + 1], c, -m_ref[qb]));
+                bf16x2 pr;
+                pr[0] = (__bf16)e0;
+                pr[1] = (__bf16)e1;
+                sum[qb] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, sum[qb], false);
+                pf[qb][v >> 3][v & 7] = pr[0];
+                pf[qb][v >> 3][(v & 7) + 1] = pr[1];
+            }
+#pragma unroll
+            for (int rd = g * 16 / G; rd < (g + 1) * 16 / G; ++rd) {
+                const int f = rd >> 1, h = rd & 1;
+                vraw[f][h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vt + voff[f % DB][h] + (f / DB) * 16 * 256));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) l_run[qb] += sum[qb];
+        PROF_MARK(0)
+
+        float mx[QB];
+        int rel[QB];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) rel[qb] = qrel[qb] - (u + 1) * kUnit;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const int f = g / QB, qb = g % QB;  // f = ks2 * DB + db
+            const s16x8 both = __builtin_shufflevector(vraw[f][0], vraw[f][1], 0, 1, 2, 3, 4, 5, 6, 7);
+            oacc[qb][f % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[qb][f / DB], oacc[qb][f % DB], 0, 0, 0);
+            const int sl = g - 2;  // the first two groups leave the last S MFMAs time to drain
+            if (sl >= 0 && sl < 4 * QB) {
+                const int q2 = sl / 4, v0 = 4 * (sl % 4);
+                if (NXT_MASK) {
+#pragma unroll
+                    for (int v = v0; v < v0 + 4; ++v) {
+                        const float x = nxt[q2][v] * c;
+                        nxt[q2][v] = (8 * (v >> 2) + (v & 3)) > rel[q2] ? -INFINITY : x;
+                    }
+                }
+                const float m3 = fmaxf(fmaxf(nxt[q2][v0], nxt[q2][v0 + 1]), nxt[q2][v0 + 2]);
+                mx[q2] = v0 == 0 ? fmaxf(m3, nxt[q2][v0 + 3]) : fmaxf(fmaxf(mx[q2], m3), nxt[q2][v0 + 3]);
+            }
+            // K fragments of unit u+2, one per group (the fragments of u+1 were consumed in phase X)
+            if (g * KSTEPS / G != (g + 1) * KSTEPS / G) {
+                const int ks = g * KSTEPS / G;
+                kf[ks] = *(const bf16x8 *)(kt2 + koff[ks]);
+            }
+            if (g == G - 3) issue_unit(u + PF, entry);  // refill: unit u+PF replaces unit u+PF-NSLOT <= u-2
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        PROF_MARK(1)
+        float bm[QB];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const float m = swap32_max(mx[qb]);
+            bm[qb] = NXT_MASK ? m : m * c;
+        }
+        move_reference(bm);
+        PROF_MARK(2)
+#ifdef ATTN_RING_PROFILE
+        wait_vmcnt<4 * (PF - 3)>();
+        PROF_MARK(3)
+#endif
+        ring_barrier();
+        PROF_MARK(4)
+    };
+    auto copy_back = [&]() {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) s_cur[qb] = s_nxt[qb];
+    };
+    int u = 0;
+    // plain units whose successor is plain too, two per trip so that the two score tiles swap roles
+    for (; u + 2 < first_masked; u += 2) {
+        iteration(u, s_cur, s_nxt, Plain{}, Plain{});
+        iteration(u + 1, s_nxt, s_cur, Plain{}, Plain{});
+    }
+    if (u + 1 < first_masked) {
+        iteration(u, s_cur, s_nxt, Plain{}, Plain{});
+        copy_back();
+        ++u;
+    }
+    if (!cur_masked) {  // the last plain unit: its successor (if any) is masked
+        iteration(u, s_cur, s_nxt, Plain{}, Masked{});
+        copy_back();
+        ++u;
+    }
+    for (; u + 1 < n_units; u += 2) {
+        iteration(u, s_cur, s_nxt, Masked{}, Masked{});
+        iteration(u + 1, s_nxt, s_cur, Masked{}, Masked{});
+    }
+    if (u < n_units) iteration(u, s_cur, s_nxt, Masked{}, Masked{});
+
+#ifdef ATTN_RING_PROFILE
+    if (lane == 0 && p.workspace) {
+        unsigned long long *dst = (unsigned long long *)p.workspace + ((size_t)blockIdx.x * 4 + wave) * 6;
+        for (int i = 0; i < 5; ++i) dst[i] = prof_t[i];
+        dst[5] = n_units;
+    }
+#endif
+    // ---- epilogue: O / l, transposed through LDS, whole rows to HBM ------------------------------
+    wait_vmcnt<0>();
+    __syncthreads();  // the ring is free: every wave is past its last V read and no DMA is in flight
+    unsigned char *stage = lds + wave * (C::kWaveTok * kHD * 2);  // [token][128] bf16, chunk-swizzled by token
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const float l = swap32_sum(l_run[qb]);
+        const float inv = l > 0.f ? 1.f / l : 0.f;
+        const int tl = qb * 32 + l32;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                bf16x2 a, b;
+                a[0] = (__bf16)(oacc[qb][db][4 * vq + 0] * inv);
+                a[1] = (__bf16)(oacc[qb][db][4 * vq + 1] * inv);
+                b[0] = (__bf16)(oacc[qb][db][4 * vq + 2] * inv);
+                b[1] = (__bf16)(oacc[qb][db][4 * vq + 3] * inv);
+                const int chunk = 4 * db + vq;  // 16-byte chunk of the row; lhalf selects its 8-byte half
+                u32x2 w;
+                w[0] = __builtin_bit_cast(uint32_t, a);
+                w[1] = __builtin_bit_cast(uint32_t, b);
+                *(u32x2 *)(stage + tl * 256 + 16 * (chunk ^ (tl & 15)) + 8 * lhalf) = w;
+            }
+        }
+    }
+    // wave-private staging: the wave's own LDS writes are ordered before its reads
+#pragma unroll
+    for (int i = 0; i < C::kWaveTok / 4; ++i) {
+        const int tl = 4 * i + (lane >> 4);
+        const int chunk = lane & 15;
+        const u32x4 row = *(const u32x4 *)(stage + tl * 256 + 16 * (chunk ^ (tl & 15)));
+        const int t = t0w + tl;
+        if (t < n_q)
+            *(u32x4 *)(obase + (int64_t)(q0 + t) * p.o_stride_tok + (int64_t)head * p.o_stride_head + 8 * chunk) = row;
+    }
+}
+
+template <int QB, int HPW, int NSLOT, int PF>
+bool ring_valid(const KParams &p)
+{
+    return p.head_dim == kHD && p.group % HPW == 0;
+}
+
+template <int QB, int HPW, int NSLOT, int PF, bool PAGED>
+hipError_t ring_launch_impl(const KParams &p, hipStream_t stream, int64_t blocks)
+{
+    using C = RingCfg<QB, HPW, NSLOT, PF>;
+    auto kern = prefill_ring_kernel<QB, HPW, NSLOT, PF, PAGED>;
+    static hipError_t attr = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::kLdsBytes);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(C::kThreads), C::kLdsBytes, stream, p);
+    return hipGetLastError();
+}
+
+template <int QB, int HPW, int NSLOT, int PF>
+hipError_t ring_launch(const KParams &p, hipStream_t stream)
+{
+    using C = RingCfg<QB, HPW, NSLOT, PF>;
+    const int64_t q_tiles = (p.max_q_len + C::kTok - 1) / C::kTok;
+    const int64_t nhg = (int64_t)p.num_kv_heads * (p.group / HPW);
+    const int64_t blocks = q_tiles * p.num_seqs * nhg;
+    if (blocks <= 0) return hipSuccess;
+    if (blocks > 0x7fffffff) return hipErrorInvalidConfiguration;
+    return p.block_table ? ring_launch_impl<QB, HPW, NSLOT, PF, true>(p, stream, blocks)
+                         : ring_launch_impl<QB, HPW, NSLOT, PF, false>(p, stream, blocks);
+}
+
+#define RING_INSTANCE(QB, HPW, NSLOT, PF)                                                                          \
+    {                                                                                                              \
+        "prefill_bf16_ring d128 qb" #QB " hpw" #HPW " slots" #NSLOT " pf" #PF, 4 * 32 * QB, kUnit, 4, HPW, PF, 0,  \
+            ring_valid<QB, HPW, NSLOT, PF>, ring_launch<QB, HPW, NSLOT, PF>                                        \
+    }
+
+}  // namespace
+
+const Instance *prefill_ring_instances(int *count)
+{
+    static const Instance table[] = {
+        RING_INSTANCE(2, 4, 8, 5), RING_INSTANCE(2, 2, 8, 5), RING_INSTANCE(2, 1, 8, 5),
+        RING_INSTANCE(2, 4, 6, 3), RING_INSTANCE(2, 4, 8, 3), RING_INSTANCE(2, 4, 8, 6),
+    };
+    *count = (int)(sizeof(table) / sizeof(table[0]));
+    return table;
+}
+
+}  // namespace attn
