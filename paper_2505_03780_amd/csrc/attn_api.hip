@@ -177,7 +177,8 @@ int heuristic(const KParams &p, int is_decode)
     if (!is_decode) {
         // pack as many heads of a KV head as divide the group: they share every K/V tile
         int hpw = p.group % 4 == 0 ? 4 : (p.group % 2 == 0 ? 2 : 1);
-        id = find_instance(0, p, 4, hpw, 32, 64 * 4, 0);                // LDS-ring kernel (D = 128)
+        id = find_instance(0, p, 8, hpw, 32, 256, 0);                   // LDS-ring kernel, two waves per SIMD (D = 128)
+        if (id < 0) id = find_instance(0, p, 4, hpw, 32, 256, 0);       // LDS-ring kernel, one wave per SIMD
         if (id < 0) id = find_instance(0, p, 4, hpw, 64, 64 * 4, 0);  // register-staged kernel
     } else {
         // enough workgroups to fill 256 CUs several times over, but parts no shorter than 256 keys

@@ -68,24 +68,27 @@ __device__ __forceinline__ void wait_vmcnt()
 // rows r..r+3 differ in the upper two bits (64-bit transposing V reads)
 __device__ __forceinline__ int swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
 
-template <int QB, int HPW, int NSLOT, int PF>
+template <int QB, int HPW, int NSLOT, int PF, int WAVES>
 struct RingCfg {
-    static constexpr int kWaves = 4;
+    static constexpr int kWaves = WAVES;
+    static constexpr int kRowsPerWave = kUnit / WAVES;   // rows of a unit that one wave transfers
+    static constexpr int kDmaPerWave = kRowsPerWave / 4;  // 1 KB transfers per wave, for K and again for V
     static constexpr int kTSub = kWaves / HPW;
     static constexpr int kWaveTok = 32 * QB;
     static constexpr int kTok = kTSub * kWaveTok;
-    static constexpr int kThreads = 256;
+    static constexpr int kThreads = WAVES * 64;
     static constexpr size_t kLdsBytes = (size_t)NSLOT * kSlotBytes;
+    static_assert(WAVES == 4 || WAVES == 8, "4 or 8 wavefronts");
     static_assert(NSLOT >= PF + 2, "ring too small for the prefetch distance");
     static_assert(PF >= 3, "K of unit u+2 is read one iteration ahead, so three units must be resident");
     static_assert(kWaves % HPW == 0, "waves must split evenly over heads");
     static_assert(kLdsBytes >= (size_t)kWaves * kWaveTok * kHD * 2, "epilogue staging must fit in the ring");
 };
 
-template <int QB, int HPW, int NSLOT, int PF, bool PAGED>
-__global__ __launch_bounds__(256) void prefill_ring_kernel(const KParams p)
+template <int QB, int HPW, int NSLOT, int PF, int WAVES, bool PAGED>
+__global__ __launch_bounds__(WAVES * 64) void prefill_ring_kernel(const KParams p)
 {
-    using C = RingCfg<QB, HPW, NSLOT, PF>;
+    using C = RingCfg<QB, HPW, NSLOT, PF, WAVES>;
     constexpr int KSTEPS = kHD / 16;
     constexpr int DB = kHD / 32;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -173,33 +176,34 @@ __global__ __launch_bounds__(256) void prefill_ring_kernel(const KParams p)
     // ---- DMA of one unit: wave w moves rows 8w..8w+7 of K and of V (2 x 1 KB each) -------------
     // The address of a transfer is a wave-uniform 64-bit base (SGPRs: pool block or packed row of the
     // unit, KV head) plus a 32-bit per-lane offset (row inside the block, swizzled 16-byte chunk).
-    // The eight rows of a wave never straddle a 16-key block, so the table entry is wave-uniform.
+    // The rows of a wave never straddle a 16-key block, so the table entry is wave-uniform.
     const unsigned char *kbase = (const unsigned char *)p.k + (int64_t)kvh * p.kv_stride_head * 2;
     const unsigned char *vbase = (const unsigned char *)p.v + (int64_t)kvh * p.kv_stride_head * 2;
     const int kv0 = PAGED ? 0 : p.kv_start_loc[s];
     const int32_t *bt_row = PAGED ? p.block_table + (int64_t)s * p.block_table_stride : nullptr;
-    const int dma_row = 8 * wave + (lane >> 4);  // + 4*i, row inside the unit
+    constexpr int RPW = C::kRowsPerWave, NDMA = C::kDmaPerWave;
+    const int dma_row = RPW * wave + (lane >> 4);  // + 4*i, row inside the unit
     const uint32_t tok_bytes = (uint32_t)p.kv_stride_tok * 2;
     const int last_unit0 = (n_kv - 1) & ~(kUnit - 1);  // first key of the last unit that holds a real key
-    uint32_t dma_chunk_off[2];
+    uint32_t dma_chunk_off[NDMA];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) dma_chunk_off[i] = 16 * ((lane & 15) ^ swz(dma_row + 4 * i));
+    for (int i = 0; i < NDMA; ++i) dma_chunk_off[i] = 16 * ((lane & 15) ^ swz(dma_row + 4 * i));
     // wave-uniform table entry of the block that holds this wave's rows of `unit` (clamped to the sequence)
     auto table_entry = [&](int unit) -> int {
         if (!PAGED) return 0;
         int u0 = unit * kUnit < last_unit0 ? unit * kUnit : last_unit0;
-        int row = u0 + 8 * wave;
+        int row = u0 + RPW * wave;
         row = row < n_kv ? row : n_kv - 1;
         return __builtin_amdgcn_readfirstlane(bt_row[row >> p.block_shift]);
     };
     auto issue_unit = [&](int unit, int entry) {
-        unsigned char *slot = lds + (unit % NSLOT) * kSlotBytes + 8 * wave * 256;
+        unsigned char *slot = lds + (unit % NSLOT) * kSlotBytes + RPW * wave * 256;
         const int u0 = unit * kUnit < last_unit0 ? unit * kUnit : last_unit0;  // units past the end repeat the last one
         // uniform part
         int64_t base;
         int first_row;  // key index that a per-lane row offset of 0 stands for
         if (PAGED) {
-            int wrow = u0 + 8 * wave;
+            int wrow = u0 + RPW * wave;
             wrow = wrow < n_kv ? wrow : n_kv - 1;
             first_row = wrow & ~(p.block_size - 1);
             base = (int64_t)entry * p.kv_stride_block * 2;
@@ -209,7 +213,7 @@ __global__ __launch_bounds__(256) void prefill_ring_kernel(const KParams p)
         }
         const unsigned char *kb = kbase + base, *vb = vbase + base;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < NDMA; ++i) {
             int row = u0 + dma_row + 4 * i;
             row = row < n_kv ? row : n_kv - 1;  // rows past the end re-read the last key (finite, masked)
             const uint32_t o = (uint32_t)(row - first_row) * tok_bytes + dma_chunk_off[i];
@@ -218,14 +222,14 @@ __global__ __launch_bounds__(256) void prefill_ring_kernel(const KParams p)
         }
     };
 
-    // Publish the ring.  Each wave issues 4 transfers per unit and memory operations complete in order,
-    // so once at most 4*(PF-3) are outstanding, this wave's transfers of every unit but the newest PF-3
+    // Publish the ring.  Each wave issues 2*NDMA transfers per unit and memory operations complete in order,
+    // so once at most 2*NDMA*(PF-3) are outstanding, this wave's transfers of every unit but the newest PF-3
     // have landed (a table load that sits between them only makes the wait stricter).  All LDS reads of
     // the slot about to be refilled have returned, because their values fed MFMAs issued earlier.  A
     // bare s_barrier is used: the fence of __syncthreads would drain vmcnt to zero and with it the
     // whole prefetch queue.
     auto ring_barrier = [&]() {
-        wait_vmcnt<4 * (PF - 3)>();
+        wait_vmcnt<2 * NDMA * (PF - 3)>();
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
     };
@@ -395,6 +399,7 @@ __global__ __launch_bounds__(256) void prefill_ring_kernel(const KParams p)
     // re-read rows of a dummy transfer and every entry is masked): no branch inside the iteration.
 #ifdef ATTN_RING_PROFILE
     unsigned long long prof_t[5] = {0, 0, 0, 0, 0}, prof_last = __builtin_readcyclecounter();
+    const unsigned long long prof_begin = prof_last;
 #define PROF_MARK(i)                                                   \
     {                                                                  \
         const unsigned long long now = __builtin_readcyclecounter();   \
@@ -424,7 +429,10 @@ __global__ __launch_bounds__(256) void prefill_ring_kernel(const KParams p)
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const int ks = g / QB, qb = g % QB;
+#ifndef EXP_SKIP_QK
             nxt[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[qb][ks], ks == 0 ? zero : nxt[qb], 0, 0, 0);
+#endif
+#ifndef EXP_SKIP_EXP
             {
                 const int v = 2 * (g / QB);
                 const float e0 = fast_exp2(CUR_MASK ? cur[qb][v] - m_ref[qb] : __builtin_fmaf(cur[qb][v], c, -m_ref[qb]));
@@ -436,11 +444,14 @@ __global__ __launch_bounds__(256) void prefill_ring_kernel(const KParams p)
                 pf[qb][v >> 3][v & 7] = pr[0];
                 pf[qb][v >> 3][(v & 7) + 1] = pr[1];
             }
+#endif
+#ifndef EXP_SKIP_TR
 #pragma unroll
             for (int rd = g * 16 / G; rd < (g + 1) * 16 / G; ++rd) {
                 const int f = rd >> 1, h = rd & 1;
                 vraw[f][h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vt + voff[f % DB][h] + (f / DB) * 16 * 256));
             }
+#endif
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
@@ -487,7 +498,7 @@ __global__ __launch_bounds__(256) void prefill_ring_kernel(const KParams p)
         move_reference(bm);
         PROF_MARK(2)
 #ifdef ATTN_RING_PROFILE
-        wait_vmcnt<4 * (PF - 3)>();
+        wait_vmcnt<2 * NDMA * (PF - 3)>();
         PROF_MARK(3)
 #endif
         ring_barrier();
@@ -521,9 +532,11 @@ __global__ __launch_bounds__(256) void prefill_ring_kernel(const KParams p)
 
 #ifdef ATTN_RING_PROFILE
     if (lane == 0 && p.workspace) {
-        unsigned long long *dst = (unsigned long long *)p.workspace + ((size_t)blockIdx.x * 4 + wave) * 6;
+        unsigned long long *dst = (unsigned long long *)p.workspace + ((size_t)blockIdx.x * 4 + wave) * 8;
         for (int i = 0; i < 5; ++i) dst[i] = prof_t[i];
         dst[5] = n_units;
+        dst[6] = __builtin_readcyclecounter() - prof_begin;
+        dst[7] = wall_clock64();
     }
 #endif
     // ---- epilogue: O / l, transposed through LDS, whole rows to HBM ------------------------------
@@ -564,40 +577,40 @@ __global__ __launch_bounds__(256) void prefill_ring_kernel(const KParams p)
     }
 }
 
-template <int QB, int HPW, int NSLOT, int PF>
+template <int QB, int HPW, int NSLOT, int PF, int WAVES>
 bool ring_valid(const KParams &p)
 {
     return p.head_dim == kHD && p.group % HPW == 0;
 }
 
-template <int QB, int HPW, int NSLOT, int PF, bool PAGED>
+template <int QB, int HPW, int NSLOT, int PF, int WAVES, bool PAGED>
 hipError_t ring_launch_impl(const KParams &p, hipStream_t stream, int64_t blocks)
 {
-    using C = RingCfg<QB, HPW, NSLOT, PF>;
-    auto kern = prefill_ring_kernel<QB, HPW, NSLOT, PF, PAGED>;
+    using C = RingCfg<QB, HPW, NSLOT, PF, WAVES>;
+    auto kern = prefill_ring_kernel<QB, HPW, NSLOT, PF, WAVES, PAGED>;
     static hipError_t attr = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::kLdsBytes);
     if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(C::kThreads), C::kLdsBytes, stream, p);
     return hipGetLastError();
 }
 
-template <int QB, int HPW, int NSLOT, int PF>
+template <int QB, int HPW, int NSLOT, int PF, int WAVES>
 hipError_t ring_launch(const KParams &p, hipStream_t stream)
 {
-    using C = RingCfg<QB, HPW, NSLOT, PF>;
+    using C = RingCfg<QB, HPW, NSLOT, PF, WAVES>;
     const int64_t q_tiles = (p.max_q_len + C::kTok - 1) / C::kTok;
     const int64_t nhg = (int64_t)p.num_kv_heads * (p.group / HPW);
     const int64_t blocks = q_tiles * p.num_seqs * nhg;
     if (blocks <= 0) return hipSuccess;
     if (blocks > 0x7fffffff) return hipErrorInvalidConfiguration;
-    return p.block_table ? ring_launch_impl<QB, HPW, NSLOT, PF, true>(p, stream, blocks)
-                         : ring_launch_impl<QB, HPW, NSLOT, PF, false>(p, stream, blocks);
+    return p.block_table ? ring_launch_impl<QB, HPW, NSLOT, PF, WAVES, true>(p, stream, blocks)
+                         : ring_launch_impl<QB, HPW, NSLOT, PF, WAVES, false>(p, stream, blocks);
 }
 
-#define RING_INSTANCE(QB, HPW, NSLOT, PF)                                                                          \
-    {                                                                                                              \
-        "prefill_bf16_ring d128 qb" #QB " hpw" #HPW " slots" #NSLOT " pf" #PF, 4 * 32 * QB, kUnit, 4, HPW, PF, 0,  \
-            ring_valid<QB, HPW, NSLOT, PF>, ring_launch<QB, HPW, NSLOT, PF>                                        \
+#define RING_INSTANCE(QB, HPW, NSLOT, PF, WAVES)                                                                  \
+    {                                                                                                             \
+        "prefill_bf16_ring d128 qb" #QB " w" #WAVES " hpw" #HPW " slots" #NSLOT " pf" #PF, WAVES * 32 * QB, kUnit, \
+            WAVES, HPW, PF, 0, ring_valid<QB, HPW, NSLOT, PF, WAVES>, ring_launch<QB, HPW, NSLOT, PF, WAVES>       \
     }
 
 }  // namespace
@@ -605,8 +618,9 @@ hipError_t ring_launch(const KParams &p, hipStream_t stream)
 const Instance *prefill_ring_instances(int *count)
 {
     static const Instance table[] = {
-        RING_INSTANCE(2, 4, 8, 5), RING_INSTANCE(2, 2, 8, 5), RING_INSTANCE(2, 1, 8, 5),
-        RING_INSTANCE(2, 4, 6, 3), RING_INSTANCE(2, 4, 8, 3), RING_INSTANCE(2, 4, 8, 6),
+        RING_INSTANCE(2, 4, 8, 5, 4), RING_INSTANCE(2, 2, 8, 5, 4), RING_INSTANCE(2, 1, 8, 5, 4),
+        RING_INSTANCE(2, 4, 8, 6, 4), RING_INSTANCE(1, 4, 8, 5, 8), RING_INSTANCE(1, 8, 8, 5, 8),
+        RING_INSTANCE(1, 2, 8, 5, 8), RING_INSTANCE(1, 1, 8, 5, 8), RING_INSTANCE(1, 4, 8, 6, 8),
     };
     *count = (int)(sizeof(table) / sizeof(table[0]));
     return table;
