@@ -36,7 +36,7 @@ namespace {
 constexpr const char *kCacheMagic = "attn-tune-cache-v1";
 // Changes whenever the kernels change in a way that invalidates old timings.
 constexpr const char *kBuildId = "k1";
-constexpr int kMinSplitLen = 256;
+constexpr int kMinSplitLen = 128;
 
 std::mutex g_mu;
 std::unordered_map<std::string, int> g_winner[2];  // [is_decode]: bucket key -> instance id
@@ -143,9 +143,35 @@ std::string bucket_key(const KParams &p, int dtype, int is_decode)
     return buf;
 }
 
+constexpr int kMaxBalancedWgs = 2048;  // workspace bound for the token-balanced decode
+
+int compute_units()
+{
+    static std::atomic<int> cached{0};
+    int cu = cached.load();
+    if (cu > 0) return cu;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return 256;
+    }
+    cached.store(prop.multiProcessorCount);
+    return prop.multiProcessorCount;
+}
+
 void apply_split(KParams &p, const Instance &inst)
 {
     int sl = inst.split_len;
+    if (sl < 0) {  // token-balanced: a fixed number of workgroups, each with an equal share of the chunks
+        const int waves = inst.waves;
+        const int head_blocks = (p.num_kv_heads + waves - 1) / waves;
+        int wgs = compute_units() * (-sl) * (8 / waves) / head_blocks;
+        wgs = std::max(1, std::min(wgs, kMaxBalancedWgs));
+        p.num_splits = wgs;
+        p.split_len = 0;
+        return;
+    }
     if (sl <= 0 || sl >= p.max_kv_len) {
         p.split_len = std::max(p.max_kv_len, 1);
         p.num_splits = 1;
@@ -181,14 +207,20 @@ int heuristic(const KParams &p, int is_decode)
         if (id < 0) id = find_instance(0, p, 4, hpw, 32, 256, 0);       // LDS-ring kernel, one wave per SIMD
         if (id < 0) id = find_instance(0, p, 4, hpw, 64, 64 * 4, 0);  // register-staged kernel
     } else {
-        // enough workgroups to fill 256 CUs several times over, but parts no shorter than 256 keys
-        const int64_t units = (int64_t)p.num_seqs * p.num_kv_heads;
-        int64_t want = units * (int64_t)p.max_kv_len / 2048;
-        int sl = kMinSplitLen;
-        while (sl * 2 <= want && sl < 4096) sl *= 2;
-        if (sl >= p.max_kv_len) sl = 0;
-        id = find_instance(1, p, 4, 16, 32, 0, sl);
-        if (id < 0) id = find_instance(1, p, 4, 16, 32, 0, 0);
+        // With four or more KV heads a workgroup can own whole cache blocks (one wavefront per head):
+        // take the token-balanced kernel, one workgroup per compute unit.  Otherwise one KV head per
+        // workgroup and fixed parts: enough workgroups to fill the chip several times over, parts no
+        // shorter than 256 keys.
+        if (p.num_kv_heads >= 4) id = find_instance(1, p, 8, 16, 32, 0, -1);
+        if (id < 0) {
+            const int64_t units = (int64_t)p.num_seqs * p.num_kv_heads;
+            int64_t want = units * (int64_t)p.max_kv_len / 2048;
+            int sl = 256;
+            while (sl * 2 <= want && sl < 4096) sl *= 2;
+            if (sl >= p.max_kv_len) sl = 0;
+            id = find_instance(1, p, 4, 16, 32, 0, sl);
+            if (id < 0) id = find_instance(1, p, 4, 16, 32, 0, 0);
+        }
     }
     if (id >= 0) return id;
     for (int i = 0; i < n; ++i)
@@ -301,11 +333,18 @@ int select_instance(const KParams &p, int dtype, int is_decode)
     return id >= 0 ? id : ATTN_ERR_UNSUPPORTED;
 }
 
+size_t balanced_workspace_bytes(int num_seqs, int num_q_heads, int head_dim, int wgs)
+{
+    return (size_t)(wgs + num_seqs) * num_q_heads * partial_stride(head_dim) * sizeof(float) + (size_t)(num_seqs + 1) * sizeof(int32_t);
+}
+
 size_t decode_workspace_bytes(int num_seqs, int num_q_heads, int head_dim, int max_kv_len)
 {
-    // sized for the shortest part any instance uses, so every instance fits
+    // sized for the shortest part any fixed-split instance uses and for the largest token-balanced
+    // launch, so every instance fits
     const int64_t splits = std::max<int64_t>(1, (max_kv_len + kMinSplitLen - 1) / kMinSplitLen);
-    return (size_t)num_seqs * num_q_heads * splits * partial_stride(head_dim) * sizeof(float);
+    const size_t fixed = (size_t)num_seqs * num_q_heads * splits * partial_stride(head_dim) * sizeof(float);
+    return std::max(fixed, balanced_workspace_bytes(num_seqs, num_q_heads, head_dim, kMaxBalancedWgs));
 }
 
 int run(const attn_args *a, int is_decode, hipStream_t stream, int instance_override)
@@ -324,13 +363,16 @@ int run(const attn_args *a, int is_decode, hipStream_t stream, int instance_over
     if (id >= n || !t[id].valid(p)) return ATTN_ERR_UNSUPPORTED;
     if (is_decode) {
         apply_split(p, t[id]);
-        if (p.num_splits > 1) {
-            const size_t need = (size_t)p.num_seqs * p.num_q_heads * p.num_splits * partial_stride(p.head_dim) * sizeof(float);
+        const bool balanced = t[id].split_len < 0;
+        if (balanced || p.num_splits > 1) {
+            const size_t need = balanced ? balanced_workspace_bytes(p.num_seqs, p.num_q_heads, p.head_dim, p.num_splits)
+                                         : (size_t)p.num_seqs * p.num_q_heads * p.num_splits * partial_stride(p.head_dim) * sizeof(float);
             if (!a->workspace || a->workspace_bytes < need) return ATTN_ERR_WORKSPACE;
         }
     }
     if (t[id].launch(p, stream) != hipSuccess) return ATTN_ERR_HIP;
-    if (is_decode && p.num_splits > 1 && launch_decode_combine(p, stream) != hipSuccess) return ATTN_ERR_HIP;
+    // fixed-split decode merges its parts with a second kernel (the token-balanced launcher brings its own)
+    if (is_decode && t[id].split_len >= 0 && p.num_splits > 1 && launch_decode_combine(p, stream) != hipSuccess) return ATTN_ERR_HIP;
     return ATTN_OK;
 }
 

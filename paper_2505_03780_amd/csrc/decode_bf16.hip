@@ -235,6 +235,375 @@ __global__ __launch_bounds__(WAVES * 64) void decode_bf16_kernel(const KParams p
     }
 }
 
+// Streams keys [k_lo, k_hi) of sequence s for KV head kvh through one wavefront and leaves the result
+// either as fp32 (partial output, max, sum) records, the one of query head h at partial_base +
+// h * head_stride, or, if partial_base is null, as the final bf16 output.
+template <int HD, int WAVES>
+__device__ __forceinline__ void decode_stream_part(const KParams &p, unsigned char *vst, int lane, int s, int kvh, int n_kv,
+                                                   int k_lo, int k_hi, float *partial_base, int64_t head_stride)
+{
+    using C = DecodeCfg<HD, WAVES>;
+    constexpr int KS = HD / 32;
+    constexpr int DB = HD / 16;
+    constexpr int VLD = kChunk * (HD / 8) / 64;
+    constexpr int VROWS = 64 / (HD / 8);
+    typedef const __attribute__((address_space(4))) int32_t *table_ptr;  // read-only, scalar loads
+    const int l16 = lane & 15;
+    const int lg = lane >> 4;
+    const int G = p.group;
+
+    bf16x8 qf[KS];
+    {
+        const __bf16 *qrow = (const __bf16 *)p.q + (int64_t)s * p.q_stride_tok +
+                             (int64_t)(kvh * G + (l16 < G ? l16 : 0)) * p.q_stride_head + 8 * lg;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            bf16x8 t = *(const bf16x8 *)(qrow + 32 * ks);
+            if (l16 >= G) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) t[e] = (__bf16)0.f;
+            }
+            qf[ks] = t;
+        }
+    }
+
+    const unsigned char *kbase = (const unsigned char *)p.k + (int64_t)kvh * p.kv_stride_head * 2;
+    const unsigned char *vbase = (const unsigned char *)p.v + (int64_t)kvh * p.kv_stride_head * 2;
+    table_ptr bt_row = (table_ptr)(p.block_table + (int64_t)s * p.block_table_stride);
+    const uint32_t tok_bytes = (uint32_t)p.kv_stride_tok * 2;
+    const int last_group = (n_kv - 1) & ~15;  // first key of the last 16-key group that holds a real key
+
+    // byte offset (wave-uniform) of the first row of the 16-key group at `key`; groups past the end of
+    // the sequence fall back to the last real group, whose rows are allocated (and masked)
+    auto group_base = [&](int key) -> int64_t {
+        key = key < last_group ? key : last_group;
+        const int blk = bt_row[key >> p.block_shift];
+        return (int64_t)blk * p.kv_stride_block * 2 + (int64_t)(key & (p.block_size - 1)) * tok_bytes;
+    };
+    // per-lane byte offsets inside a group: K in MFMA A-operand order, V fully coalesced
+    const uint32_t k_lane = (uint32_t)l16 * tok_bytes + 16 * lg;
+    uint32_t v_lane[VLD];
+#pragma unroll
+    for (int i = 0; i < VLD; ++i) {
+        const int row = lane / (HD / 8) + VROWS * i;
+        v_lane[i] = (uint32_t)(row & 15) * tok_bytes + 16 * (lane % (HD / 8));
+    }
+
+    struct Regs {
+        u32x4 k[2][KS];
+        u32x4 v[VLD];
+    };
+    auto load = [&](Regs &r, int64_t g0, int64_t g1) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const unsigned char *kr = kbase + (t ? g1 : g0) + k_lane;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) r.k[t][ks] = *(const u32x4 *)(kr + 64 * ks);
+        }
+#pragma unroll
+        for (int i = 0; i < VLD; ++i) {
+            const int row = lane / (HD / 8) + VROWS * i;
+            r.v[i] = *(const u32x4 *)(vbase + (row < 16 ? g0 : g1) + v_lane[i]);
+        }
+    };
+
+    f32x4 oacc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) oacc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = -INFINITY, l_run = 0.f;
+    const int v_rd = (4 * lg + (l16 >> 2)) * C::kVPitch + 8 * (l16 & 3);
+
+    f32x4 sacc[2];
+    // consume: the chunk leaves its registers (K into the score MFMAs, V into the wave's LDS tile), so
+    // the same registers can take the loads of the chunk after next right away
+    auto consume = [&](Regs &r, int c0) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            sacc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                sacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.k[t][ks]), qf[ks], sacc[t], 0, 0, 0);
+        }
+        const bool tail = c0 + kChunk > k_hi;
+#pragma unroll
+        for (int i = 0; i < VLD; ++i) {
+            const int row = lane / (HD / 8) + VROWS * i;
+            // rows past the end may hold anything (even NaN): their weight is 0, so store zeros
+            const u32x4 val = (tail && c0 + row >= k_hi) ? u32x4{0u, 0u, 0u, 0u} : r.v[i];
+            *(u32x4 *)(vst + row * C::kVPitch + 16 * (lane % (HD / 8))) = val;
+        }
+    };
+    auto finish = [&](int c0) {
+        const bool tail = c0 + kChunk > k_hi;
+        float x[8];
+        float mloc = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                float y = sacc[t][v] * p.scale_log2e;
+                if (tail && c0 + 16 * t + 4 * lg + v >= k_hi) y = -INFINITY;
+                x[4 * t + v] = y;
+                mloc = fmaxf(mloc, y);
+            }
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+        const float m_new = fmaxf(m_run, mloc);  // finite: key c0 < k_hi is unmasked
+        const float alpha = fast_exp2(m_run - m_new);
+        m_run = m_new;
+        bf16x8 pf;
+        float rowsum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float w = fast_exp2(x[e] - m_new);
+            rowsum += w;
+            pf[e] = (__bf16)w;
+        }
+        l_run = l_run * alpha + rowsum;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) oacc[db] *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            const unsigned char *a = vst + v_rd + db * 32;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)a);
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a + 16 * C::kVPitch));
+            const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            oacc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, both), pf, oacc[db], 0, 0, 0);
+        }
+    };
+
+    // chunk i covers keys [k_lo + 32 i, +32).  Two register sets alternate; a set is reloaded with the
+    // chunk after next as soon as it has been consumed, so about two chunks (32 KB per wave) are in flight.
+    const int nch = (k_hi - k_lo + kChunk - 1) / kChunk;
+    Regs ra, rb;
+    {
+        const int64_t a0 = group_base(k_lo), a1 = group_base(k_lo + 16);
+        const int64_t b0 = group_base(k_lo + 32), b1 = group_base(k_lo + 48);
+        if (nch > 0) load(ra, a0, a1);
+        if (nch > 1) load(rb, b0, b1);
+    }
+    // bases of the chunk that is loaded next: fetched (scalar loads) one step before they are needed
+    int64_t gn0 = group_base(k_lo + 2 * kChunk), gn1 = group_base(k_lo + 2 * kChunk + 16);
+    for (int i = 0; i < nch; i += 2) {
+        const int c = k_lo + kChunk * i;
+        int64_t t0 = group_base(c + 3 * kChunk), t1 = group_base(c + 3 * kChunk + 16);
+        consume(ra, c);
+        if (i + 2 < nch) load(ra, gn0, gn1);
+        gn0 = t0, gn1 = t1;
+        finish(c);
+        if (i + 1 < nch) {
+            t0 = group_base(c + 4 * kChunk), t1 = group_base(c + 4 * kChunk + 16);
+            consume(rb, c + kChunk);
+            if (i + 3 < nch) load(rb, gn0, gn1);
+            gn0 = t0, gn1 = t1;
+            finish(c + kChunk);
+        }
+    }
+
+    // ---- this wave's result: G heads x HD channels, no other wave involved ---------------------------
+    l_run += __shfl_xor(l_run, 16);
+    l_run += __shfl_xor(l_run, 32);
+    if (l16 < G) {
+        const int head = kvh * G + l16;
+        if (partial_base == nullptr) {
+            __bf16 *o = (__bf16 *)p.out + (int64_t)s * p.o_stride_tok + (int64_t)head * p.o_stride_head;
+            const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+                bf16x4 w;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) w[v] = (__bf16)(oacc[db][v] * inv);
+                *(bf16x4 *)(o + db * 16 + 4 * lg) = w;
+            }
+        } else {
+            float *w = partial_base + (int64_t)head * head_stride;
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                // (HD + 2) floats per record: 8-byte aligned, so two 8-byte stores per block of 4
+                *(float2 *)(w + db * 16 + 4 * lg) = float2{oacc[db][0], oacc[db][1]};
+                *(float2 *)(w + db * 16 + 4 * lg + 2) = float2{oacc[db][2], oacc[db][3]};
+            }
+            if (lg == 0) {
+                w[HD] = m_run;
+                w[HD + 1] = l_run;
+            }
+        }
+    }
+}
+
+// Variant that keeps a whole KV-cache block together: a workgroup owns (sequence, part) and its
+// wavefront w owns KV head w, so the eight 256-byte head slices of a token row are fetched by one
+// workgroup at about the same time (whole 32 KB blocks per 16 keys instead of scattered slices), and
+// no wavefront ever waits for another: there is no barrier and no cross-wave reduction.  About two
+// chunks per wavefront are in flight in registers (two alternating register sets, reloaded as soon
+// as consumed), and block-table entries are read through the scalar cache one step ahead of the
+// loads that need them.
+template <int HD, int WAVES>
+__global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void decode_seq_kernel(const KParams p)
+{
+    using C = DecodeCfg<HD, WAVES>;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[WAVES * C::kVBytes];
+    const int head_blocks = (p.num_kv_heads + WAVES - 1) / WAVES;
+    int bid = blockIdx.x;
+    const int hb = bid % head_blocks;
+    bid /= head_blocks;
+    const int s = bid % p.num_seqs;
+    const int part = bid / p.num_seqs;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int kvh = hb * WAVES + wave;
+    if (kvh >= p.num_kv_heads) return;
+    const int n_kv = p.seq_lens[s];
+    const int k_lo = part * p.split_len;
+    if (k_lo >= n_kv && part != 0) return;
+    const int k_hi = k_lo + p.split_len < n_kv ? k_lo + p.split_len : n_kv;
+    float *partial = p.num_splits == 1 ? nullptr
+                                       : p.workspace + ((int64_t)s * p.num_q_heads * p.num_splits + part) * (HD + 2);
+    // records of one sequence are laid out [head][part]
+    decode_stream_part<HD, WAVES>(p, lds + wave * C::kVBytes, lane, s, kvh, n_kv, k_lo, k_hi, partial,
+                                  (int64_t)p.num_splits * (HD + 2));
+}
+
+// Token-balanced variant: the key axis of the whole batch, cut into 32-key chunks and laid end to
+// end, is divided evenly over the workgroups (one per compute unit and KV-head block), whatever the
+// mix of sequence lengths.  A workgroup therefore walks a run of chunks that may start in the middle
+// of one sequence and end in the middle of another; every (workgroup, sequence) piece leaves one
+// partial record with the unique index  workgroup + sequence  (both only grow along the walk).  The
+// chunk prefix sums of the batch are recomputed by every wavefront (a 64-wide scan over seq_lens) and
+// written once for the combine kernel.
+//   workspace: [num_wgs + num_seqs][Hq][HD + 2] floats, then int32 chunk prefix sums [num_seqs + 1].
+template <int HD, int WAVES>
+__global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void decode_balanced_kernel(const KParams p)
+{
+    using C = DecodeCfg<HD, WAVES>;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[WAVES * C::kVBytes];
+    const int head_blocks = (p.num_kv_heads + WAVES - 1) / WAVES;
+    const int hb = blockIdx.x % head_blocks;
+    const int w = blockIdx.x / head_blocks;
+    const int num_wgs = p.num_splits;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int kvh = hb * WAVES + wave;
+    const int B = p.num_seqs;
+    int32_t *prefix_out = (int32_t *)(p.workspace + (int64_t)(num_wgs + B) * p.num_q_heads * (HD + 2));
+    const bool writer = blockIdx.x == 0 && wave == 0;
+
+    // pass 1: total number of chunks (every wavefront on its own: no barrier in this kernel)
+    int total = 0;
+    for (int g0 = 0; g0 < B; g0 += 64) {
+        const int i = g0 + lane;
+        int c = i < B ? (p.seq_lens[i] + kChunk - 1) / kChunk : 0;
+        int incl = c;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(incl, o);
+            if (lane >= o) incl += t;
+        }
+        if (writer && i < B) prefix_out[i] = total + incl - c;
+        total += __builtin_amdgcn_readlane(incl, 63);
+    }
+    if (writer && lane == 0) prefix_out[B] = total;
+    if (kvh >= p.num_kv_heads) return;
+    const int per_wg = (total + num_wgs - 1) / num_wgs;
+    const int x0 = w * per_wg;
+    int x1 = x0 + per_wg < total ? x0 + per_wg : total;
+    if (x0 >= x1) return;
+
+    // pass 2: the sequence that holds chunk x0, and the offset of x0 inside it
+    int s = 0, off = 0;
+    {
+        int base = 0;
+        for (int g0 = 0; g0 < B; g0 += 64) {
+            const int i = g0 + lane;
+            const int c = i < B ? (p.seq_lens[i] + kChunk - 1) / kChunk : 0;
+            int incl = c;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int t = __shfl_up(incl, o);
+                if (lane >= o) incl += t;
+            }
+            const int grp = __builtin_amdgcn_readlane(incl, 63);
+            if (x0 < base + grp) {
+                // first lane whose inclusive prefix exceeds x0
+                const unsigned long long m = __builtin_amdgcn_ballot_w64(base + incl > x0);
+                const int idx = __builtin_ctzll(m);
+                const int excl = __builtin_amdgcn_readlane(incl - c, idx);
+                s = g0 + idx;
+                off = x0 - (base + excl);
+                break;
+            }
+            base += grp;
+        }
+    }
+
+    // walk the pieces
+    int remaining = x1 - x0;
+    while (remaining > 0) {
+        const int n_kv = p.seq_lens[s];
+        const int nc = (n_kv + kChunk - 1) / kChunk;
+        const int n = remaining < nc - off ? remaining : nc - off;
+        if (n > 0) {
+            const int k_lo = off * kChunk;
+            const int k_hi = (off + n) * kChunk < n_kv ? (off + n) * kChunk : n_kv;
+            float *partial = p.workspace + (int64_t)(w + s) * p.num_q_heads * (HD + 2);
+            decode_stream_part<HD, WAVES>(p, lds + wave * C::kVBytes, lane, s, kvh, n_kv, k_lo, k_hi, partial, HD + 2);
+            remaining -= n;
+        }
+        ++s;
+        off = 0;
+    }
+}
+
+// Combine for the token-balanced variant: the pieces of sequence s are the workgroups that overlap its
+// chunk range, at record indices workgroup + s.
+template <int HD>
+__global__ __launch_bounds__(64) void decode_balanced_combine_kernel(const KParams p)
+{
+    const int head = blockIdx.x % p.num_q_heads;
+    const int s = blockIdx.x / p.num_q_heads;
+    const int lane = threadIdx.x;
+    const int num_wgs = p.num_splits;
+    const int B = p.num_seqs;
+    const int32_t *prefix = (const int32_t *)(p.workspace + (int64_t)(num_wgs + B) * p.num_q_heads * (HD + 2));
+    const int c0 = prefix[s], c1 = prefix[s + 1], total = prefix[B];
+    constexpr int CPL = HD / 64;
+    __bf16 *o = (__bf16 *)p.out + (int64_t)s * p.o_stride_tok + (int64_t)head * p.o_stride_head;
+    if (c1 <= c0) {  // empty context: zeros
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) o[CPL * lane + c] = (__bf16)0.f;
+        return;
+    }
+    const int per_wg = (total + num_wgs - 1) / num_wgs;
+    const int w0 = c0 / per_wg, w1 = (c1 - 1) / per_wg;
+    const int parts = w1 - w0 + 1;
+    const int64_t stride = (int64_t)p.num_q_heads * (HD + 2);
+    const float *rec = p.workspace + (int64_t)(w0 + s) * stride + (int64_t)head * (HD + 2);
+    float M = -INFINITY;
+    for (int i = lane; i < parts; i += 64) M = fmaxf(M, rec[i * stride + HD]);
+#pragma unroll
+    for (int sh = 32; sh > 0; sh >>= 1) M = fmaxf(M, __shfl_xor(M, sh));
+    float L = 0.f;
+    for (int i = lane; i < parts; i += 64) {
+        const float mi = rec[i * stride + HD];
+        L += mi == -INFINITY ? 0.f : rec[i * stride + HD + 1] * fast_exp2(mi - M);
+    }
+#pragma unroll
+    for (int sh = 32; sh > 0; sh >>= 1) L += __shfl_xor(L, sh);
+    float acc[CPL];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) acc[c] = 0.f;
+    for (int i = 0; i < parts; ++i) {
+        const float mi = rec[i * stride + HD];
+        const float sc = mi == -INFINITY ? 0.f : fast_exp2(mi - M);
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) acc[c] += rec[i * stride + CPL * lane + c] * sc;
+    }
+    const float inv = L > 0.f ? 1.f / L : 0.f;
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) o[CPL * lane + c] = (__bf16)(acc[c] * inv);
+}
+
 // One wavefront per (sequence, query head): merges the split-K parts.
 //   M = max_s m_s,  L = sum_s l_s 2^(m_s - M),  out = sum_s O_s 2^(m_s - M) / L
 // Parts that hold no key were never written and are not read.
@@ -292,6 +661,46 @@ hipError_t decode_launch(const KParams &p, hipStream_t stream)
     return hipGetLastError();
 }
 
+template <int HD, int WAVES>
+hipError_t decode_seq_launch(const KParams &p, hipStream_t stream)
+{
+    const int64_t head_blocks = (p.num_kv_heads + WAVES - 1) / WAVES;
+    const int64_t blocks = head_blocks * p.num_seqs * p.num_splits;
+    if (blocks <= 0) return hipSuccess;
+    if (blocks > 0x7fffffff) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((decode_seq_kernel<HD, WAVES>), dim3((unsigned)blocks), dim3(WAVES * 64), 0, stream, p);
+    return hipGetLastError();
+}
+
+// Token-balanced launch: p.num_splits carries the number of workgroups per KV-head block (set by the
+// dispatcher from the compute-unit count); the combine kernel follows on the same stream.
+template <int HD, int WAVES>
+hipError_t decode_balanced_launch(const KParams &p, hipStream_t stream)
+{
+    const int64_t head_blocks = (p.num_kv_heads + WAVES - 1) / WAVES;
+    const int64_t blocks = head_blocks * p.num_splits;
+    if (blocks <= 0 || p.num_seqs <= 0) return hipSuccess;
+    if (blocks > 0x7fffffff) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((decode_balanced_kernel<HD, WAVES>), dim3((unsigned)blocks), dim3(WAVES * 64), 0, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(decode_balanced_combine_kernel<HD>, dim3((unsigned)(p.num_seqs * p.num_q_heads)), dim3(64), 0, stream, p);
+    return hipGetLastError();
+}
+
+// SPLIT < 0 marks the token-balanced variant with -SPLIT workgroups per compute unit
+#define DECODE_BAL_INSTANCE(HD, WAVES, PER_CU)                                                                  \
+    {                                                                                                          \
+        "decode_bf16_balanced d" #HD " w" #WAVES " percu" #PER_CU, 16, kChunk, WAVES, 16, 2, -PER_CU,            \
+            decode_valid<HD, WAVES>, decode_balanced_launch<HD, WAVES>                                         \
+    }
+
+#define DECODE_SEQ_INSTANCE(HD, WAVES, SPLIT)                                                                  \
+    {                                                                                                          \
+        "decode_bf16_seq d" #HD " w" #WAVES " split" #SPLIT, 16, kChunk, WAVES, 16, 2, SPLIT, decode_valid<HD, WAVES>, \
+            decode_seq_launch<HD, WAVES>                                                                       \
+    }
+
 #define DECODE_INSTANCE(HD, WAVES, SPLIT)                                                                     \
     {                                                                                                         \
         "decode_bf16 d" #HD " w" #WAVES " split" #SPLIT, 16, kChunk, WAVES, 16, 2, SPLIT, decode_valid<HD, WAVES>, \
@@ -323,6 +732,12 @@ const Instance *decode_instances(int *count)
         DECODE_INSTANCE(128, 8, 2048), DECODE_INSTANCE(128, 8, 4096), DECODE_INSTANCE(128, 2, 256),
         DECODE_INSTANCE(128, 2, 512),  DECODE_INSTANCE(128, 2, 1024), DECODE_INSTANCE(64, 4, 0),
         DECODE_INSTANCE(64, 4, 512),   DECODE_INSTANCE(64, 4, 2048),
+        DECODE_SEQ_INSTANCE(128, 8, 0),    DECODE_SEQ_INSTANCE(128, 8, 128),  DECODE_SEQ_INSTANCE(128, 8, 256),
+        DECODE_SEQ_INSTANCE(128, 8, 512),  DECODE_SEQ_INSTANCE(128, 8, 1024), DECODE_SEQ_INSTANCE(128, 8, 2048),
+        DECODE_SEQ_INSTANCE(128, 4, 256),  DECODE_SEQ_INSTANCE(128, 4, 512),  DECODE_SEQ_INSTANCE(128, 4, 1024),
+        DECODE_SEQ_INSTANCE(64, 8, 256),   DECODE_SEQ_INSTANCE(64, 4, 512),
+        DECODE_BAL_INSTANCE(128, 8, 1),    DECODE_BAL_INSTANCE(128, 8, 2),    DECODE_BAL_INSTANCE(128, 4, 1),
+        DECODE_BAL_INSTANCE(128, 4, 2),    DECODE_BAL_INSTANCE(64, 8, 1),     DECODE_BAL_INSTANCE(64, 4, 2),
     };
     *count = (int)(sizeof(table) / sizeof(table[0]));
     return table;

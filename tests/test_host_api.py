@@ -45,8 +45,13 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layout_matches_and_workspace_bytes():
     a = _paged(total_q=4, max_q_len=1, max_kv_len=4096)
-    # 4 seqs * 32 heads * ceil(4096/256) parts * (128 + 2) floats
-    assert A.attn_workspace_bytes(a, True) == 4 * 32 * 16 * 130 * 4
+    # the larger of: fixed splits, 4 seqs * 32 heads * ceil(4096/128) parts * (128 + 2) floats; and the
+    # token-balanced launch, (2048 workgroups + 4 seqs) * 32 heads * 130 floats + 5 chunk prefix sums
+    fixed = 4 * 32 * 32 * 130 * 4
+    balanced = (2048 + 4) * 32 * 130 * 4 + 5 * 4
+    assert A.attn_workspace_bytes(a, True) == max(fixed, balanced)
+    long = _paged(num_seqs=64, total_q=64, max_q_len=1, max_kv_len=32768, block_table_stride=2048)
+    assert A.attn_workspace_bytes(long, True) == 64 * 32 * 256 * 130 * 4
     assert A.attn_workspace_bytes(a, False) == 0
     a.struct_bytes += 8
     assert A.attn_workspace_bytes(a, True) == 0
@@ -112,8 +117,12 @@ def test_instance_tables_and_heuristic_selection():
     # long-context decode with few sequences takes split-K; short contexts do not split
     long = _paged(num_seqs=16, total_q=16, max_q_len=1, max_kv_len=32768, block_table_stride=2048, num_q_heads=64)
     assert "split0" not in names_d[A.attn_selected_instance(long, True)]
+    # with eight KV heads the default is the token-balanced kernel (one workgroup per compute unit)
+    assert "balanced" in names_d[A.attn_selected_instance(long, True)]
     short = _paged(num_seqs=512, total_q=512, max_q_len=1, max_kv_len=200)
-    assert "split0" in names_d[A.attn_selected_instance(short, True)]
+    assert "balanced" in names_d[A.attn_selected_instance(short, True)]
+    few_heads = _paged(num_seqs=512, total_q=512, max_q_len=1, max_kv_len=200, num_q_heads=4, num_kv_heads=1)
+    assert "split0" in names_d[A.attn_selected_instance(few_heads, True)]
     # a forced instance that does not fit the shape is refused, not silently replaced
     d64 = next(i for i, n in enumerate(names_p) if "d64" in n)
     A.attn_force_instance(False, d64)
