@@ -57,6 +57,20 @@ __device__ __forceinline__ float swap32_sum(float x)
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// Transposing LDS read issued behind the compiler's back.  The compiler cannot tell that this read
+// never touches a ring slot with a transfer in flight and would drain the whole prefetch queue
+// (s_waitcnt vmcnt(0)) in front of the builtin; as inline assembly it is not tracked at all, so the
+// consumer must wait for it explicitly with lds_wait() before using the value.
+__device__ __forceinline__ s16x4 lds_read_tr16_b64_untracked(const unsigned char *p)
+{
+    s16x4 r;
+    const unsigned addr = (unsigned)(uintptr_t)(__attribute__((address_space(3))) const unsigned char *)p;
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(r) : "v"(addr) : "memory");
+    return r;
+}
+// all LDS operations of this wave have returned; ties the registers so that their uses stay below
+__device__ __forceinline__ void lds_wait(s16x4 &a, s16x4 &b) { asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b)::"memory"); }
+
 // s_waitcnt with only vmcnt constrained (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
@@ -77,7 +91,9 @@ struct RingCfg {
     static constexpr int kWaveTok = 32 * QB;
     static constexpr int kTok = kTSub * kWaveTok;
     static constexpr int kThreads = WAVES * 64;
-    static constexpr size_t kLdsBytes = (size_t)NSLOT * kSlotBytes;
+    static constexpr int kImgBytes = 8192;               // V^T fragments of one unit, in MFMA operand order
+    static constexpr int kFragsPerWave = 8 / WAVES;      // fragments each wave transposes per unit
+    static constexpr size_t kLdsBytes = (size_t)NSLOT * kSlotBytes + 2 * kImgBytes;
     static_assert(WAVES == 4 || WAVES == 8, "4 or 8 wavefronts");
     static_assert(NSLOT >= PF + 2, "ring too small for the prefetch distance");
     static_assert(PF >= 3, "K of unit u+2 is read one iteration ahead, so three units must be resident");
@@ -230,8 +246,39 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_ring_kernel(const KParams 
     // whole prefetch queue.
     auto ring_barrier = [&]() {
         wait_vmcnt<2 * NDMA * (PF - 3)>();
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this wave's LDS write of transposed V has been performed
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
+    };
+    // V^T fragment images: a wave transposes its share of the V fragments of a unit once
+    // (ds_read_b64_tr_b16, the slow path) and stores them in MFMA A-operand order; every wave then
+    // fetches all eight fragments with plain 128-bit reads.  Two images alternate.
+    unsigned char *img_base = lds + NSLOT * kSlotBytes;
+    auto transpose_load = [&](int unit, s16x4 (&raw)[C::kFragsPerWave][2]) {
+        const unsigned char *vt = lds + (unit % NSLOT) * kSlotBytes;
+#pragma unroll
+        for (int i = 0; i < C::kFragsPerWave; ++i) {
+            const int f = wave * C::kFragsPerWave + i;  // f = ks2 * DB + db
+            const int db = f % DB, ks2 = f / DB;
+            // voff is indexed with a compile-time db in the main loop; here db depends on the wave
+            const int a = l16 >> 2, h1 = (lane >> 4) & 1, h0 = (lane & 3) >> 1;
+#pragma unroll
+            for (int rd = 0; rd < 2; ++rd) {
+                const int o = kVOff + (8 * rd + 4 * lhalf + a) * 256 + 16 * (((db ^ a) << 2) | (2 * (h1 ^ rd)) | (h0 ^ lhalf)) +
+                              8 * (lane & 1) + ks2 * 16 * 256;
+                raw[i][rd] = lds_read_tr16_b64_untracked(vt + o);
+            }
+        }
+    };
+    auto transpose_store = [&](int unit, s16x4 (&raw)[C::kFragsPerWave][2]) {
+        unsigned char *img = img_base + (unit & 1) * C::kImgBytes;
+#pragma unroll
+        for (int i = 0; i < C::kFragsPerWave; ++i) {
+            lds_wait(raw[i][0], raw[i][1]);
+            const int f = wave * C::kFragsPerWave + i;
+            const s16x8 both = __builtin_shufflevector(raw[i][0], raw[i][1], 0, 1, 2, 3, 4, 5, 6, 7);
+            *(s16x8 *)(img + f * 1024 + lane * 16) = both;
+        }
     };
 
     // ---- per-lane LDS read offsets ----------------------------------------------------------------
@@ -241,17 +288,6 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_ring_kernel(const KParams 
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) koff[ks] = l32 * 256 + 16 * ((2 * ks + lhalf) ^ kx);
     }
-    int voff[DB][2];
-    {
-        const int a = l16 >> 2, h1 = (lane >> 4) & 1, h0 = (lane & 3) >> 1;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int rd = 0; rd < 2; ++rd)
-                voff[db][rd] = kVOff + (8 * rd + 4 * lhalf + a) * 256 +
-                               16 * (((db ^ a) << 2) | (2 * (h1 ^ rd)) | (h0 ^ lhalf)) + 8 * (lane & 1);
-    }
-
     // ---- state ---------------------------------------------------------------------------------------
     f32x16 oacc[QB][DB];
     f32x16 s_cur[QB], s_nxt[QB];
@@ -280,22 +316,6 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_ring_kernel(const KParams 
         for (int ks = 0; ks < KSTEPS; ++ks) {
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[qb][ks], sacc[qb], 0, 0, 0);
-        }
-    };
-    // O^T += V(u)^T P^T
-    auto pv = [&](int unit, const bf16x8 (&pf)[QB][2]) {
-        const unsigned char *vt = lds + (unit % NSLOT) * kSlotBytes;
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vt + voff[db][0] + ks * 16 * 256));
-                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vt + voff[db][1] + ks * 16 * 256));
-                const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb) oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][ks], oacc[qb][db], 0, 0, 0);
-            }
         }
     };
     // Move the reference of the rows whose new maximum outgrew it by more than the slack; rare, and
@@ -382,6 +402,14 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_ring_kernel(const KParams 
     bf16x8 kf[KSTEPS];  // K fragments of the next unit, fetched one iteration ahead
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) kf[ks] = *(const bf16x8 *)(lds + (1 % NSLOT) * kSlotBytes + koff[ks]);
+    {
+        s16x4 raw[C::kFragsPerWave][2];
+        transpose_load(0, raw);
+        transpose_store(0, raw);
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+    }
 
     // ---- main loop ------------------------------------------------------------------------------------
     // Invariant at the top of iteration u: S(u) settled in `cur`; units u and u+1 resident; units up to
@@ -413,12 +441,13 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_ring_kernel(const KParams 
         constexpr bool CUR_MASK = decltype(cur_tag)::value;
         constexpr bool NXT_MASK = decltype(nxt_tag)::value;
         constexpr int G = 8 * QB;  // MFMAs per product
-        const unsigned char *vt = lds + (u % NSLOT) * kSlotBytes;
+        const unsigned char *img = img_base + (u & 1) * C::kImgBytes + lane * 16;
         const unsigned char *kt2 = lds + ((u + 2) % NSLOT) * kSlotBytes;
         const int entry = table_entry(u + PF);  // scalar load, consumed at the end of phase Y
 
         bf16x8 pf[QB][2];
-        s16x4 vraw[2 * DB][2];
+        bf16x8 vfrag[2 * DB];
+        s16x4 raw[C::kFragsPerWave][2];
         float sum[QB];
         bf16x2 ones;
         ones[0] = (__bf16)1.f;
@@ -445,13 +474,11 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_ring_kernel(const KParams 
                 pf[qb][v >> 3][(v & 7) + 1] = pr[1];
             }
 #endif
-#ifndef EXP_SKIP_TR
-#pragma unroll
-            for (int rd = g * 16 / G; rd < (g + 1) * 16 / G; ++rd) {
-                const int f = rd >> 1, h = rd & 1;
-                vraw[f][h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vt + voff[f % DB][h] + (f / DB) * 16 * 256));
+            if (g * 8 / G != (g + 1) * 8 / G) {
+                const int f = g * 8 / G;
+                vfrag[f] = *(const bf16x8 *)(img + f * 1024);
             }
-#endif
+            if (g == 1) transpose_load(u + 1, raw);  // this wave's share of V(u+1), stored late in phase Y
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
@@ -465,8 +492,9 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_ring_kernel(const KParams 
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const int f = g / QB, qb = g % QB;  // f = ks2 * DB + db
-            const s16x8 both = __builtin_shufflevector(vraw[f][0], vraw[f][1], 0, 1, 2, 3, 4, 5, 6, 7);
-            oacc[qb][f % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[qb][f / DB], oacc[qb][f % DB], 0, 0, 0);
+#ifndef EXP_SKIP_PV
+            oacc[qb][f % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfrag[f], pf[qb][f / DB], oacc[qb][f % DB], 0, 0, 0);
+#endif
             const int sl = g - 2;  // the first two groups leave the last S MFMAs time to drain
             if (sl >= 0 && sl < 4 * QB) {
                 const int q2 = sl / 4, v0 = 4 * (sl % 4);
@@ -486,6 +514,7 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_ring_kernel(const KParams 
                 kf[ks] = *(const bf16x8 *)(kt2 + koff[ks]);
             }
             if (g == G - 3) issue_unit(u + PF, entry);  // refill: unit u+PF replaces unit u+PF-NSLOT <= u-2
+            if (g == G - 2) transpose_store(u + 1, raw);  // image (u+1)&1 was last read in iteration u-1
             __builtin_amdgcn_sched_barrier(0);
         }
         PROF_MARK(1)
@@ -532,7 +561,7 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_ring_kernel(const KParams 
 
 #ifdef ATTN_RING_PROFILE
     if (lane == 0 && p.workspace) {
-        unsigned long long *dst = (unsigned long long *)p.workspace + ((size_t)blockIdx.x * 4 + wave) * 8;
+        unsigned long long *dst = (unsigned long long *)p.workspace + ((size_t)blockIdx.x * WAVES + wave) * 8;
         for (int i = 0; i < 5; ++i) dst[i] = prof_t[i];
         dst[5] = n_units;
         dst[6] = __builtin_readcyclecounter() - prof_begin;
