@@ -81,7 +81,7 @@ typedef struct attn_args {
 
     const int32_t *block_table; /* int32 [B, block_table_stride]; entries past ceil(seq_len/block_size) are never read */
     int32_t block_table_stride;
-    int32_t block_size; /* paged: a multiple of 16 */
+    int32_t block_size; /* paged: a power of two, at least 16 */
     int32_t num_blocks; /* pool size, used only for validation */
 
     const int32_t *query_start_loc; /* int32 [B+1], exclusive prefix sum of n_q; decode: ignored (n_q = 1) */
@@ -128,8 +128,11 @@ size_t attn_workspace_bytes(const attn_args *args, int is_decode);
  * critical path, keep results in a reusable cache that records its
  * environment).  Times every valid compiled kernel instance for the shape
  * bucket of `shape_like` on synthetic device buffers that this call allocates
- * and frees itself (pointer fields of shape_like are ignored; lengths are
- * spread uniformly up to max_q_len / max_kv_len), records the fastest, and, if
+ * and frees itself.  Of the pointer fields of shape_like only seq_lens and (for
+ * prefill) query_start_loc are used, if not NULL: the tuning batch then has the
+ * caller's own lengths (copied to the host; they must respect max_q_len and
+ * max_kv_len).  Otherwise lengths are spread evenly between half of and the full
+ * max_q_len / max_kv_len.  The call records the fastest instance and, if
  * cache_path is not NULL, merges it into that file (atomic replace).  `iters`
  * timed launches per instance (<= 0: a default).  Synchronous; not capturable.
  * flags: bit 0 = print one line per instance to stderr.

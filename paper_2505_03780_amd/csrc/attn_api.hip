@@ -417,9 +417,25 @@ int tune(const attn_args *shape, int is_decode, const char *cache_path, int iter
     const int max_q = is_decode ? 1 : std::max(1, shape->max_q_len);
     const int max_kv = std::max(shape->max_kv_len, max_q);
 
-    // synthetic lengths: spread evenly between half of the maximum and the maximum
+    // lengths: the caller's own batch if it passes seq_lens (and query_start_loc for prefill), else
+    // spread evenly between half of the maximum and the maximum
     std::vector<int32_t> qsl(B + 1, 0), kvsl(B + 1, 0), lens(B);
-    for (int s = 0; s < B; ++s) {
+    bool have_lens = false;
+    if (shape->seq_lens && (is_decode || shape->query_start_loc)) {
+        std::vector<int32_t> hl(B), hq(B + 1, 0);
+        have_lens = hipMemcpy(hl.data(), shape->seq_lens, B * sizeof(int32_t), hipMemcpyDeviceToHost) == hipSuccess;
+        if (have_lens && !is_decode)
+            have_lens = hipMemcpy(hq.data(), shape->query_start_loc, (B + 1) * sizeof(int32_t), hipMemcpyDeviceToHost) == hipSuccess;
+        if (!have_lens) (void)hipGetLastError();
+        for (int s = 0; s < B && have_lens; ++s) {
+            const int nq = is_decode ? 1 : hq[s + 1] - hq[s];
+            if (nq < 0 || nq > max_q || hl[s] < nq || hl[s] > max_kv) have_lens = false;  // disagrees with the bounds: ignore
+            qsl[s + 1] = qsl[s] + nq;
+            kvsl[s + 1] = kvsl[s] + hl[s];
+            lens[s] = hl[s];
+        }
+    }
+    for (int s = 0; s < B && !have_lens; ++s) {
         const double f = B > 1 ? 0.5 + 0.5 * (double)((s * 7) % B) / (B - 1) : 1.0;
         int nq = is_decode ? 1 : std::max(1, (int)(max_q * f));
         int nkv = std::max(nq, (int)(max_kv * f));
