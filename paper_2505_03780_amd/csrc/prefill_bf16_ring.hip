@@ -95,14 +95,16 @@ struct RingCfg {
     static constexpr int kFragsPerWave = 8 / WAVES;      // fragments each wave transposes per unit
     static constexpr size_t kLdsBytes = (size_t)NSLOT * kSlotBytes + 2 * kImgBytes;
     static_assert(WAVES == 4 || WAVES == 8, "4 or 8 wavefronts");
-    static_assert(NSLOT >= PF + 2, "ring too small for the prefetch distance");
+    // during iteration u the slots of units u+1 (V, transposed for the next iteration) and u+2 (K) are
+    // read and units u+3..u+PF are in flight; unit u+PF reuses the slot of unit u+PF-NSLOT <= u
+    static_assert(NSLOT >= PF, "ring too small for the prefetch distance");
     static_assert(PF >= 3, "K of unit u+2 is read one iteration ahead, so three units must be resident");
     static_assert(kWaves % HPW == 0, "waves must split evenly over heads");
     static_assert(kLdsBytes >= (size_t)kWaves * kWaveTok * kHD * 2, "epilogue staging must fit in the ring");
 };
 
 template <int QB, int HPW, int NSLOT, int PF, int WAVES, bool PAGED>
-__global__ __launch_bounds__(WAVES * 64) void prefill_ring_kernel(const KParams p)
+__global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void prefill_ring_kernel(const KParams p)
 {
     using C = RingCfg<QB, HPW, NSLOT, PF, WAVES>;
     constexpr int KSTEPS = kHD / 16;
@@ -513,7 +515,7 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_ring_kernel(const KParams 
                 const int ks = g * KSTEPS / G;
                 kf[ks] = *(const bf16x8 *)(kt2 + koff[ks]);
             }
-            if (g == G - 3) issue_unit(u + PF, entry);  // refill: unit u+PF replaces unit u+PF-NSLOT <= u-2
+            if (g == G - 3) issue_unit(u + PF, entry);  // refill: unit u+PF replaces unit u+PF-NSLOT <= u
             if (g == G - 2) transpose_store(u + 1, raw);  // image (u+1)&1 was last read in iteration u-1
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -650,6 +652,8 @@ const Instance *prefill_ring_instances(int *count)
         RING_INSTANCE(2, 4, 8, 5, 4), RING_INSTANCE(2, 2, 8, 5, 4), RING_INSTANCE(2, 1, 8, 5, 4),
         RING_INSTANCE(2, 4, 8, 6, 4), RING_INSTANCE(1, 4, 8, 5, 8), RING_INSTANCE(1, 8, 8, 5, 8),
         RING_INSTANCE(1, 2, 8, 5, 8), RING_INSTANCE(1, 1, 8, 5, 8), RING_INSTANCE(1, 4, 8, 6, 8),
+        RING_INSTANCE(1, 4, 8, 8, 8), RING_INSTANCE(1, 1, 8, 8, 8), RING_INSTANCE(1, 4, 4, 4, 4),
+        RING_INSTANCE(1, 1, 4, 4, 4), RING_INSTANCE(1, 2, 4, 4, 4),
     };
     *count = (int)(sizeof(table) / sizeof(table[0]));
     return table;
