@@ -182,14 +182,14 @@ void apply_split(KParams &p, const Instance &inst)
 }
 
 // ---- built-in heuristic (used until a bucket has been tuned) -----------------------------------
-int find_instance(int is_decode, const KParams &p, int waves, int hpw, int bn, int bm, int split_len)
+int find_instance(int is_decode, const KParams &p, int waves, int hpw, int bn, int bm, int split_len, int order = 0)
 {
     int n;
     const Instance *t = instances(is_decode, &n);
     for (int i = 0; i < n; ++i) {
         if (!t[i].valid(p)) continue;
         if (t[i].waves == waves && t[i].heads_per_wg == hpw && t[i].block_n == bn && (bm <= 0 || t[i].block_m == bm) &&
-            t[i].split_len == split_len)
+            t[i].split_len == split_len && t[i].order == order)
             return i;
     }
     return -1;
@@ -203,8 +203,11 @@ int heuristic(const KParams &p, int is_decode)
     if (!is_decode) {
         // pack as many heads of a KV head as divide the group: they share every K/V tile
         int hpw = p.group % 4 == 0 ? 4 : (p.group % 2 == 0 ? 2 : 1);
-        id = find_instance(0, p, 8, hpw, 32, 256, 0);                   // LDS-ring kernel, two waves per SIMD (D = 128)
-        if (id < 0) id = find_instance(0, p, 4, hpw, 32, 256, 0);       // LDS-ring kernel, one wave per SIMD
+        // a cached prefix that dominates the key range is streamed once per query tile: run the tiles of
+        // a sequence side by side so that they share it in L2
+        const int order = p.block_table && p.max_kv_len >= 2 * p.max_q_len ? 1 : 0;
+        id = find_instance(0, p, 8, hpw, 32, 256, 0, order);              // LDS-ring kernel, two waves per SIMD (D = 128)
+        if (id < 0) id = find_instance(0, p, 4, hpw, 32, 256, 0, order);  // LDS-ring kernel, one wave per SIMD
         if (id < 0) id = find_instance(0, p, 4, hpw, 64, 64 * 4, 0);  // register-staged kernel
     } else {
         // With four or more KV heads a workgroup can own whole cache blocks (one wavefront per head):

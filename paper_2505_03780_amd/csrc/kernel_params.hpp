@@ -35,6 +35,9 @@ struct KParams {
     float *workspace;
     int32_t num_splits;  // parts the key axis is cut into (grid dimension)
     int32_t split_len;   // keys per part, a multiple of the kernel's key tile
+    // prefill grid order: 0 = query tiles outermost (the longest tiles of all sequences start first),
+    // 1 = sequences outermost (all tiles of a sequence run together and share its K/V in one L2)
+    int32_t tile_order;
 };
 
 // One ahead-of-time compiled template instance: the unit the autotuner sweeps
@@ -51,6 +54,7 @@ struct Instance {
     int split_len;  // decode: keys per split-K part (0 = never split); prefill: 0
     bool (*valid)(const KParams &);
     hipError_t (*launch)(const KParams &, hipStream_t);
+    int order;  // prefill: KParams::tile_order this instance launches with; decode: 0
 };
 
 const Instance *prefill_instances(int *count);         // all prefill instances, ring variants first

@@ -112,15 +112,23 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
     // ---- which (head group, sequence, query tile) ---------------------------------------------
+    // Workgroups go to the eight XCDs round-robin, so with the KV head innermost every XCD (and its
+    // own L2) serves one KV head when Hkv is a multiple or a divisor of eight.
     const int groups_per_kvh = p.group / HPW;
-    const int nhg = p.num_kv_heads * groups_per_kvh;
     int bid = blockIdx.x;
-    const int hg = bid % nhg;
-    bid /= nhg;
-    const int s = bid % p.num_seqs;
-    const int r = bid / p.num_seqs;
-    const int kvh = hg % p.num_kv_heads;
-    const int hsub = hg / p.num_kv_heads;
+    const int kvh = bid % p.num_kv_heads;
+    bid /= p.num_kv_heads;
+    const int hsub = bid % groups_per_kvh;
+    bid /= groups_per_kvh;
+    int s, r;
+    if (p.tile_order == 0) {
+        s = bid % p.num_seqs;
+        r = bid / p.num_seqs;
+    } else {
+        const int q_tiles = (p.max_q_len + C::kTok - 1) / C::kTok;
+        r = bid % q_tiles;
+        s = bid / q_tiles;
+    }
 
     const int q0 = p.query_start_loc[s];
     const int n_q = p.query_start_loc[s + 1] - q0;
@@ -625,9 +633,11 @@ hipError_t ring_launch_impl(const KParams &p, hipStream_t stream, int64_t blocks
     return hipGetLastError();
 }
 
-template <int QB, int HPW, int NSLOT, int PF, int WAVES>
-hipError_t ring_launch(const KParams &p, hipStream_t stream)
+template <int QB, int HPW, int NSLOT, int PF, int WAVES, int ORDER>
+hipError_t ring_launch(const KParams &p_in, hipStream_t stream)
 {
+    KParams p = p_in;
+    p.tile_order = ORDER;
     using C = RingCfg<QB, HPW, NSLOT, PF, WAVES>;
     const int64_t q_tiles = (p.max_q_len + C::kTok - 1) / C::kTok;
     const int64_t nhg = (int64_t)p.num_kv_heads * (p.group / HPW);
@@ -638,11 +648,14 @@ hipError_t ring_launch(const KParams &p, hipStream_t stream)
                          : ring_launch_impl<QB, HPW, NSLOT, PF, WAVES, false>(p, stream, blocks);
 }
 
-#define RING_INSTANCE(QB, HPW, NSLOT, PF, WAVES)                                                                  \
-    {                                                                                                             \
-        "prefill_bf16_ring d128 qb" #QB " w" #WAVES " hpw" #HPW " slots" #NSLOT " pf" #PF, WAVES * 32 * QB, kUnit, \
-            WAVES, HPW, PF, 0, ring_valid<QB, HPW, NSLOT, PF, WAVES>, ring_launch<QB, HPW, NSLOT, PF, WAVES>       \
+#define RING_ONE(QB, HPW, NSLOT, PF, WAVES, ORDER, TAG)                                                                  \
+    {                                                                                                                    \
+        "prefill_bf16_ring d128 qb" #QB " w" #WAVES " hpw" #HPW " slots" #NSLOT " pf" #PF TAG, WAVES * 32 * QB, kUnit,    \
+            WAVES, HPW, PF, 0, ring_valid<QB, HPW, NSLOT, PF, WAVES>, ring_launch<QB, HPW, NSLOT, PF, WAVES, ORDER>, ORDER \
     }
+// both grid orders of one compiled kernel
+#define RING_INSTANCE(QB, HPW, NSLOT, PF, WAVES) \
+    RING_ONE(QB, HPW, NSLOT, PF, WAVES, 0, ""), RING_ONE(QB, HPW, NSLOT, PF, WAVES, 1, " seqmajor")
 
 }  // namespace
 
