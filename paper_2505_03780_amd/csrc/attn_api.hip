@@ -182,14 +182,14 @@ void apply_split(KParams &p, const Instance &inst)
 }
 
 // ---- built-in heuristic (used until a bucket has been tuned) -----------------------------------
-int find_instance(int is_decode, const KParams &p, int waves, int hpw, int bn, int bm, int split_len, int order = 0)
+int find_instance(int is_decode, const KParams &p, int waves, int hpw, int bn, int bm, int split_len, int variant = 0)
 {
     int n;
     const Instance *t = instances(is_decode, &n);
     for (int i = 0; i < n; ++i) {
         if (!t[i].valid(p)) continue;
         if (t[i].waves == waves && t[i].heads_per_wg == hpw && t[i].block_n == bn && (bm <= 0 || t[i].block_m == bm) &&
-            t[i].split_len == split_len && t[i].order == order)
+            t[i].split_len == split_len && t[i].variant == variant)
             return i;
     }
     return -1;

@@ -252,6 +252,24 @@ __device__ __forceinline__ void decode_stream_part(const KParams &p, unsigned ch
     const int lg = lane >> 4;
     const int G = p.group;
 
+    if (k_hi <= k_lo) {  // no key (an empty context): the empty result, and no table entry is touched
+        if (l16 < G) {
+            const int head = kvh * G + l16;
+            if (partial_base == nullptr) {
+                __bf16 *o = (__bf16 *)p.out + (int64_t)s * p.o_stride_tok + (int64_t)head * p.o_stride_head;
+                for (int d = 4 * lg; d < HD; d += 16) *(uint2 *)(o + d) = uint2{0u, 0u};
+            } else {
+                float *w = partial_base + (int64_t)head * head_stride;
+                for (int d = 4 * lg; d < HD; d += 16) {
+                    *(float2 *)(w + d) = float2{0.f, 0.f};
+                    *(float2 *)(w + d + 2) = float2{0.f, 0.f};
+                }
+                if (lg == 0) *(float2 *)(w + HD) = float2{-INFINITY, 0.f};
+            }
+        }
+        return;
+    }
+
     bf16x8 qf[KS];
     {
         const __bf16 *qrow = (const __bf16 *)p.q + (int64_t)s * p.q_stride_tok +
@@ -424,10 +442,7 @@ __device__ __forceinline__ void decode_stream_part(const KParams &p, unsigned ch
                 *(float2 *)(w + db * 16 + 4 * lg) = float2{oacc[db][0], oacc[db][1]};
                 *(float2 *)(w + db * 16 + 4 * lg + 2) = float2{oacc[db][2], oacc[db][3]};
             }
-            if (lg == 0) {
-                w[HD] = m_run;
-                w[HD + 1] = l_run;
-            }
+            if (lg == 0) *(float2 *)(w + HD) = float2{m_run, l_run};
         }
     }
 }
@@ -463,6 +478,89 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void decode_seq_kernel(const
     // records of one sequence are laid out [head][part]
     decode_stream_part<HD, WAVES>(p, lds + wave * C::kVBytes, lane, s, kvh, n_kv, k_lo, k_hi, partial,
                                   (int64_t)p.num_splits * (HD + 2));
+}
+
+// Merge of the `parts` records of one query head by a group of 16 lanes (`sub` = lane within the
+// group, all 16 active); the record of part i starts at r + i * stride.  Lane `sub` owns channels
+// [HD/16 * sub, + HD/16) of the result, written as bf16 to o (already offset to those channels).
+//   M = max_i m_i,  L = sum_i l_i 2^(m_i - M),  out = sum_i O_i 2^(m_i - M) / L
+// Parts go in blocks of 16: each lane fetches one (m, l) pair and its channels of all 16 partial
+// outputs at once, and the block's scales come from one 16-lane reduction, so the merge costs one
+// memory round trip per block instead of several per part.  A part that was never written must not be passed;
+// m = -inf (a part without keys) gets weight zero.
+template <int HD>
+__device__ __forceinline__ void merge_head(const float *r, int parts, int64_t stride, int lane, __bf16 *o)
+{
+    constexpr int CPL = HD / 16;
+    const int sub = lane & 15;
+    auto load2 = [](const float *src) -> float2 { return *(const float2 *)src; };
+    auto group_max = [](float x) {
+#pragma unroll
+        for (int sh = 1; sh < 16; sh <<= 1) x = fmaxf(x, __shfl_xor(x, sh));
+        return x;
+    };
+    auto group_sum = [](float x) {
+#pragma unroll
+        for (int sh = 1; sh < 16; sh <<= 1) x += __shfl_xor(x, sh);
+        return x;
+    };
+    float acc[CPL];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) acc[c] = 0.f;
+    float M = -INFINITY, L = 0.f;
+    for (int b0 = 0; b0 < parts; b0 += 16) {
+        const int nb = parts - b0 < 16 ? parts - b0 : 16;
+        // every load of the block is issued before the first result is needed: one round trip per block
+        const float2 ml = sub < nb ? load2(r + (int64_t)(b0 + sub) * stride + HD) : float2{-INFINITY, 0.f};
+        float2 d[16][CPL / 2];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const float *rj = r + (int64_t)(b0 + j) * stride + CPL * sub;
+#pragma unroll
+            for (int c = 0; c < CPL / 2; ++c) d[j][c] = j < nb ? load2(rj + 2 * c) : float2{0.f, 0.f};
+        }
+        const float m_new = fmaxf(M, group_max(ml.x));
+        if (m_new == -INFINITY) continue;  // nothing but empty parts so far (uniform over the group)
+        const float keep = fast_exp2(M - m_new);  // 0 for the first block
+        const float sc = fast_exp2(ml.x - m_new);  // 0 for lanes past the block and for empty parts
+        L = L * keep + group_sum(ml.y * sc);
+        M = m_new;
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) acc[c] *= keep;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const float wj = __shfl(sc, (lane & 48) | j);
+#pragma unroll
+            for (int c = 0; c < CPL / 2; ++c) {
+                acc[2 * c] += d[j][c].x * wj;
+                acc[2 * c + 1] += d[j][c].y * wj;
+            }
+        }
+    }
+    const float inv = L > 0.f ? 1.f / L : 0.f;
+    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+    for (int c = 0; c < CPL; c += 4) {
+        bf16x4 w4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w4[e] = (__bf16)(acc[c + e] * inv);
+        *(bf16x4 *)(o + c) = w4;
+    }
+}
+
+// One wavefront merges the G query heads of (sequence s, KV head kvh), four heads at a time.
+// rec = record of part 0 at this KV head's first query head; head_stride / part_stride in floats.
+template <int HD>
+__device__ __forceinline__ void merge_group(const KParams &p, int lane, int s, int kvh, const float *rec, int parts, int64_t head_stride,
+                                            int64_t part_stride)
+{
+    const int G = p.group;
+    for (int h0 = 0; h0 < G; h0 += 4) {
+        const int hl = h0 + (lane >> 4);
+        const int hc = hl < G ? hl : G - 1;  // idle groups repeat the last head (same values, same address)
+        __bf16 *o = (__bf16 *)p.out + (int64_t)s * p.o_stride_tok + (int64_t)(kvh * G + hc) * p.o_stride_head + (HD / 16) * (lane & 15);
+        merge_head<HD>(rec + (int64_t)hc * head_stride, parts, part_stride, lane, o);
+    }
 }
 
 // Token-balanced variant: the key axis of the whole batch, cut into 32-key chunks and laid end to
@@ -556,92 +654,39 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void decode_balanced_kernel(
 }
 
 // Combine for the token-balanced variant: the pieces of sequence s are the workgroups that overlap its
-// chunk range, at record indices workgroup + s.
+// chunk range, at record indices workgroup + s.  One wavefront per (sequence, KV head).
 template <int HD>
 __global__ __launch_bounds__(64) void decode_balanced_combine_kernel(const KParams p)
 {
-    const int head = blockIdx.x % p.num_q_heads;
-    const int s = blockIdx.x / p.num_q_heads;
+    const int kvh = blockIdx.x % p.num_kv_heads;
+    const int s = blockIdx.x / p.num_kv_heads;
     const int lane = threadIdx.x;
     const int num_wgs = p.num_splits;
     const int B = p.num_seqs;
     const int32_t *prefix = (const int32_t *)(p.workspace + (int64_t)(num_wgs + B) * p.num_q_heads * (HD + 2));
     const int c0 = prefix[s], c1 = prefix[s + 1], total = prefix[B];
-    constexpr int CPL = HD / 64;
-    __bf16 *o = (__bf16 *)p.out + (int64_t)s * p.o_stride_tok + (int64_t)head * p.o_stride_head;
-    if (c1 <= c0) {  // empty context: zeros
-#pragma unroll
-        for (int c = 0; c < CPL; ++c) o[CPL * lane + c] = (__bf16)0.f;
-        return;
-    }
     const int per_wg = (total + num_wgs - 1) / num_wgs;
-    const int w0 = c0 / per_wg, w1 = (c1 - 1) / per_wg;
-    const int parts = w1 - w0 + 1;
+    // an empty context has no piece: parts = 0 makes the merge write zeros
+    const int w0 = c1 > c0 ? c0 / per_wg : 0;
+    const int parts = c1 > c0 ? (c1 - 1) / per_wg - w0 + 1 : 0;
     const int64_t stride = (int64_t)p.num_q_heads * (HD + 2);
-    const float *rec = p.workspace + (int64_t)(w0 + s) * stride + (int64_t)head * (HD + 2);
-    float M = -INFINITY;
-    for (int i = lane; i < parts; i += 64) M = fmaxf(M, rec[i * stride + HD]);
-#pragma unroll
-    for (int sh = 32; sh > 0; sh >>= 1) M = fmaxf(M, __shfl_xor(M, sh));
-    float L = 0.f;
-    for (int i = lane; i < parts; i += 64) {
-        const float mi = rec[i * stride + HD];
-        L += mi == -INFINITY ? 0.f : rec[i * stride + HD + 1] * fast_exp2(mi - M);
-    }
-#pragma unroll
-    for (int sh = 32; sh > 0; sh >>= 1) L += __shfl_xor(L, sh);
-    float acc[CPL];
-#pragma unroll
-    for (int c = 0; c < CPL; ++c) acc[c] = 0.f;
-    for (int i = 0; i < parts; ++i) {
-        const float mi = rec[i * stride + HD];
-        const float sc = mi == -INFINITY ? 0.f : fast_exp2(mi - M);
-#pragma unroll
-        for (int c = 0; c < CPL; ++c) acc[c] += rec[i * stride + CPL * lane + c] * sc;
-    }
-    const float inv = L > 0.f ? 1.f / L : 0.f;
-#pragma unroll
-    for (int c = 0; c < CPL; ++c) o[CPL * lane + c] = (__bf16)(acc[c] * inv);
+    merge_group<HD>(p, lane, s, kvh, p.workspace + (int64_t)(w0 + s) * stride + (int64_t)kvh * p.group * (HD + 2), parts, HD + 2, stride);
 }
 
-// One wavefront per (sequence, query head): merges the split-K parts.
-//   M = max_s m_s,  L = sum_s l_s 2^(m_s - M),  out = sum_s O_s 2^(m_s - M) / L
-// Parts that hold no key were never written and are not read.
+// Combine for the fixed-split kernels, one wavefront per (sequence, KV head): records are laid out
+// [sequence][head][part].  Parts that hold no key were never written and are not read.
 template <int HD>
 __global__ __launch_bounds__(64) void decode_combine_kernel(const KParams p)
 {
-    const int head = blockIdx.x % p.num_q_heads;
-    const int s = blockIdx.x / p.num_q_heads;
+    const int kvh = blockIdx.x % p.num_kv_heads;
+    const int s = blockIdx.x / p.num_kv_heads;
     const int lane = threadIdx.x;
     const int n_kv = p.seq_lens[s];
     int parts = (n_kv + p.split_len - 1) / p.split_len;
-    parts = parts < 1 ? 1 : parts;
-    const float *w = p.workspace + ((int64_t)s * p.num_q_heads + head) * p.num_splits * (HD + 2);
-    float M = -INFINITY;
-    for (int i = lane; i < parts; i += 64) M = fmaxf(M, w[i * (HD + 2) + HD]);
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
-    float L = 0.f;
-    for (int i = lane; i < parts; i += 64) {
-        const float mi = w[i * (HD + 2) + HD];
-        L += mi == -INFINITY ? 0.f : w[i * (HD + 2) + HD + 1] * fast_exp2(mi - M);
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) L += __shfl_xor(L, o);
-    constexpr int CPL = HD / 64;
-    float acc[CPL];
-#pragma unroll
-    for (int c = 0; c < CPL; ++c) acc[c] = 0.f;
-    for (int i = 0; i < parts; ++i) {
-        const float mi = w[i * (HD + 2) + HD];
-        const float sc = mi == -INFINITY ? 0.f : fast_exp2(mi - M);
-#pragma unroll
-        for (int c = 0; c < CPL; ++c) acc[c] += w[i * (HD + 2) + CPL * lane + c] * sc;
-    }
-    __bf16 *o = (__bf16 *)p.out + (int64_t)s * p.o_stride_tok + (int64_t)head * p.o_stride_head;
-    const float inv = L > 0.f ? 1.f / L : 0.f;
-#pragma unroll
-    for (int c = 0; c < CPL; ++c) o[CPL * lane + c] = (__bf16)(acc[c] * inv);
+    parts = parts < 1 ? 1 : parts;  // part 0 is always written (m = -inf, l = 0 for an empty context)
+    const int64_t head_stride = (int64_t)p.num_splits * (HD + 2);
+    merge_group<HD>(p, lane, s, kvh, p.workspace + ((int64_t)s * p.num_q_heads + (int64_t)kvh * p.group) * head_stride, parts,
+                           head_stride, HD + 2);
 }
 
 template <int HD, int WAVES>
@@ -684,7 +729,7 @@ hipError_t decode_balanced_launch(const KParams &p, hipStream_t stream)
     hipLaunchKernelGGL((decode_balanced_kernel<HD, WAVES>), dim3((unsigned)blocks), dim3(WAVES * 64), 0, stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(decode_balanced_combine_kernel<HD>, dim3((unsigned)(p.num_seqs * p.num_q_heads)), dim3(64), 0, stream, p);
+    hipLaunchKernelGGL(decode_balanced_combine_kernel<HD>, dim3((unsigned)(p.num_seqs * p.num_kv_heads)), dim3(64), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -711,7 +756,7 @@ hipError_t decode_balanced_launch(const KParams &p, hipStream_t stream)
 
 hipError_t launch_decode_combine(const KParams &p, hipStream_t stream)
 {
-    const int64_t blocks = (int64_t)p.num_seqs * p.num_q_heads;
+    const int64_t blocks = (int64_t)p.num_seqs * p.num_kv_heads;
     if (blocks <= 0) return hipSuccess;
     if (blocks > 0x7fffffff) return hipErrorInvalidConfiguration;
     if (p.head_dim == 128)

@@ -54,7 +54,7 @@ struct Instance {
     int split_len;  // decode: keys per split-K part (0 = never split); prefill: 0
     bool (*valid)(const KParams &);
     hipError_t (*launch)(const KParams &, hipStream_t);
-    int order;  // prefill: KParams::tile_order this instance launches with; decode: 0
+    int variant;  // prefill: KParams::tile_order this instance launches with; decode: 0
 };
 
 const Instance *prefill_instances(int *count);         // all prefill instances, ring variants first

@@ -123,6 +123,37 @@ def test_decode_peaked_and_one_short_sequence_with_many_splits():
         assert_close(to_host_f64(dw.run(True)), ref, "bf16", A.attn_instance_name(True, i))
 
 
+def test_decode_two_batches_take_turns_on_one_workspace():
+    """Nothing a decode call leaves in the workspace may matter to the next one, whatever its shape."""
+    big = W.make_paged(43, "decode", np.ones(6, np.int32), [3000, 1, 2500, 40, 1777, 900], 32, 8, 128, 16, 700)
+    small = W.make_paged(44, "decode", np.ones(3, np.int32), [513, 64, 1200], 32, 8, 128, 16, 200)
+    dwb, dws = DeviceWorkload(big), DeviceWorkload(small)
+    refb, refs = oracle.attention(oracle_problem(big)), oracle.attention(oracle_problem(small))
+    dwb.args(True)
+    dws.ws = dwb.ws  # large enough for the smaller batch: args() keeps it
+    for i in _valid_instances(dwb, True):
+        A.attn_force_instance(True, i)
+        for rep in range(2):
+            assert_close(to_host_f64(dwb.run(True)), refb, "bf16", "big %d rep %d" % (i, rep))
+            assert_close(to_host_f64(dws.run(True)), refs, "bf16", "small %d rep %d" % (i, rep))
+    assert dws.ws is dwb.ws
+
+
+def test_decode_writes_zeros_for_contexts_without_keys():
+    lens = [1, 700, 1, 1500, 33]
+    wl = W.make_paged(45, "decode", np.ones(5, np.int32), lens, 32, 8, 128, 16, 300)
+    dw = DeviceWorkload(wl)
+    ref = oracle.attention(oracle_problem(wl))
+    dw.seq_lens[0] = 0
+    dw.seq_lens[2] = 0
+    for i in _valid_instances(dw, True):
+        name = A.attn_instance_name(True, i)
+        A.attn_force_instance(True, i)
+        got = to_host_f64(dw.run(True))
+        assert np.all(got[0] == 0) and np.all(got[2] == 0), name
+        assert_close(got[[1, 3, 4]], ref[[1, 3, 4]], "bf16", name)
+
+
 # ---- the benchmark configurations at full size ------------------------------------------------
 
 def test_config2_decode_8b_full_size():
