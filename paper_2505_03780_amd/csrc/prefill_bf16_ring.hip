@@ -468,10 +468,7 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const int ks = g / QB, qb = g % QB;
-#ifndef EXP_SKIP_QK
             nxt[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[qb][ks], ks == 0 ? zero : nxt[qb], 0, 0, 0);
-#endif
-#ifndef EXP_SKIP_EXP
             {
                 const int v = 2 * (g / QB);
                 const float e0 = fast_exp2(CUR_MASK ? cur[qb][v] - m_ref[qb] : __builtin_fmaf(cur[qb][v], c, -m_ref[qb]));
@@ -483,7 +480,6 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
                 pf[qb][v >> 3][v & 7] = pr[0];
                 pf[qb][v >> 3][(v & 7) + 1] = pr[1];
             }
-#endif
             if (g * 8 / G != (g + 1) * 8 / G) {
                 const int f = g * 8 / G;
                 vfrag[f] = *(const bf16x8 *)(img + f * 1024);
@@ -502,9 +498,7 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const int f = g / QB, qb = g % QB;  // f = ks2 * DB + db
-#ifndef EXP_SKIP_PV
             oacc[qb][f % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfrag[f], pf[qb][f / DB], oacc[qb][f % DB], 0, 0, 0);
-#endif
             const int sl = g - 2;  // the first two groups leave the last S MFMAs time to drain
             if (sl >= 0 && sl < 4 * QB) {
                 const int q2 = sl / 4, v0 = 4 * (sl % 4);
