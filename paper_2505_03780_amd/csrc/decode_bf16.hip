@@ -480,56 +480,56 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void decode_seq_kernel(const
                                   (int64_t)p.num_splits * (HD + 2));
 }
 
-// Merge of the `parts` records of one query head by a group of 16 lanes (`sub` = lane within the
-// group, all 16 active); the record of part i starts at r + i * stride.  Lane `sub` owns channels
-// [HD/16 * sub, + HD/16) of the result, written as bf16 to o (already offset to those channels).
+// Merge of the `parts` records of one query head by half a wavefront (32 lanes, all active; `sub` =
+// lane within the half); the record of part i starts at r + i * stride.  Lane `sub` owns channels
+// [HD/32 * sub, + HD/32) of the result, written as bf16 to o (already offset to those channels).
 //   M = max_i m_i,  L = sum_i l_i 2^(m_i - M),  out = sum_i O_i 2^(m_i - M) / L
-// Parts go in blocks of 16: each lane fetches one (m, l) pair and its channels of all 16 partial
-// outputs at once, and the block's scales come from one 16-lane reduction, so the merge costs one
-// memory round trip per block instead of several per part.  A part that was never written must not be passed;
-// m = -inf (a part without keys) gets weight zero.
+// Parts go in blocks of 32: each lane fetches one (m, l) pair and its channels of all 32 partial
+// outputs at once, and the block's scales come from one 32-lane reduction, so the merge costs one
+// memory round trip per block instead of several per part.  A part that was never written must not
+// be passed; m = -inf (a part without keys) gets weight zero.
 template <int HD>
 __device__ __forceinline__ void merge_head(const float *r, int parts, int64_t stride, int lane, __bf16 *o)
 {
-    constexpr int CPL = HD / 16;
-    const int sub = lane & 15;
+    constexpr int CPL = HD / 32;  // 4 or 2 channels per lane
+    const int sub = lane & 31;
     auto load2 = [](const float *src) -> float2 { return *(const float2 *)src; };
-    auto group_max = [](float x) {
+    auto half_max = [](float x) {
 #pragma unroll
-        for (int sh = 1; sh < 16; sh <<= 1) x = fmaxf(x, __shfl_xor(x, sh));
+        for (int sh = 1; sh < 32; sh <<= 1) x = fmaxf(x, __shfl_xor(x, sh));
         return x;
     };
-    auto group_sum = [](float x) {
+    auto half_sum = [](float x) {
 #pragma unroll
-        for (int sh = 1; sh < 16; sh <<= 1) x += __shfl_xor(x, sh);
+        for (int sh = 1; sh < 32; sh <<= 1) x += __shfl_xor(x, sh);
         return x;
     };
     float acc[CPL];
 #pragma unroll
     for (int c = 0; c < CPL; ++c) acc[c] = 0.f;
     float M = -INFINITY, L = 0.f;
-    for (int b0 = 0; b0 < parts; b0 += 16) {
-        const int nb = parts - b0 < 16 ? parts - b0 : 16;
+    for (int b0 = 0; b0 < parts; b0 += 32) {
+        const int nb = parts - b0 < 32 ? parts - b0 : 32;
         // every load of the block is issued before the first result is needed: one round trip per block
         const float2 ml = sub < nb ? load2(r + (int64_t)(b0 + sub) * stride + HD) : float2{-INFINITY, 0.f};
-        float2 d[16][CPL / 2];
+        float2 d[32][CPL / 2];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
+        for (int j = 0; j < 32; ++j) {
             const float *rj = r + (int64_t)(b0 + j) * stride + CPL * sub;
 #pragma unroll
             for (int c = 0; c < CPL / 2; ++c) d[j][c] = j < nb ? load2(rj + 2 * c) : float2{0.f, 0.f};
         }
-        const float m_new = fmaxf(M, group_max(ml.x));
-        if (m_new == -INFINITY) continue;  // nothing but empty parts so far (uniform over the group)
+        const float m_new = fmaxf(M, half_max(ml.x));
+        if (m_new == -INFINITY) continue;  // nothing but empty parts so far (uniform over the half)
         const float keep = fast_exp2(M - m_new);  // 0 for the first block
         const float sc = fast_exp2(ml.x - m_new);  // 0 for lanes past the block and for empty parts
-        L = L * keep + group_sum(ml.y * sc);
+        L = L * keep + half_sum(ml.y * sc);
         M = m_new;
 #pragma unroll
         for (int c = 0; c < CPL; ++c) acc[c] *= keep;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const float wj = __shfl(sc, (lane & 48) | j);
+        for (int j = 0; j < 32; ++j) {
+            const float wj = __shfl(sc, (lane & 32) | j);
 #pragma unroll
             for (int c = 0; c < CPL / 2; ++c) {
                 acc[2 * c] += d[j][c].x * wj;
@@ -538,29 +538,24 @@ __device__ __forceinline__ void merge_head(const float *r, int parts, int64_t st
         }
     }
     const float inv = L > 0.f ? 1.f / L : 0.f;
-    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+    typedef __bf16 bf16xC __attribute__((ext_vector_type(CPL)));
+    bf16xC w;
 #pragma unroll
-    for (int c = 0; c < CPL; c += 4) {
-        bf16x4 w4;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) w4[e] = (__bf16)(acc[c + e] * inv);
-        *(bf16x4 *)(o + c) = w4;
-    }
+    for (int c = 0; c < CPL; ++c) w[c] = (__bf16)(acc[c] * inv);
+    *(bf16xC *)o = w;
 }
 
-// One wavefront merges the G query heads of (sequence s, KV head kvh), four heads at a time.
+// One wavefront merges query heads 2*pair and 2*pair + 1 of the G heads of (sequence s, KV head kvh).
 // rec = record of part 0 at this KV head's first query head; head_stride / part_stride in floats.
 template <int HD>
-__device__ __forceinline__ void merge_group(const KParams &p, int lane, int s, int kvh, const float *rec, int parts, int64_t head_stride,
-                                            int64_t part_stride)
+__device__ __forceinline__ void merge_pair(const KParams &p, int lane, int s, int kvh, int pair, const float *rec, int parts,
+                                           int64_t head_stride, int64_t part_stride)
 {
     const int G = p.group;
-    for (int h0 = 0; h0 < G; h0 += 4) {
-        const int hl = h0 + (lane >> 4);
-        const int hc = hl < G ? hl : G - 1;  // idle groups repeat the last head (same values, same address)
-        __bf16 *o = (__bf16 *)p.out + (int64_t)s * p.o_stride_tok + (int64_t)(kvh * G + hc) * p.o_stride_head + (HD / 16) * (lane & 15);
-        merge_head<HD>(rec + (int64_t)hc * head_stride, parts, part_stride, lane, o);
-    }
+    const int hl = 2 * pair + (lane >> 5);
+    const int hc = hl < G ? hl : G - 1;  // an idle half repeats the last head (same values, same address)
+    __bf16 *o = (__bf16 *)p.out + (int64_t)s * p.o_stride_tok + (int64_t)(kvh * G + hc) * p.o_stride_head + (HD / 32) * (lane & 31);
+    merge_head<HD>(rec + (int64_t)hc * head_stride, parts, part_stride, lane, o);
 }
 
 // Token-balanced variant: the key axis of the whole batch, cut into 32-key chunks and laid end to
@@ -654,12 +649,16 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void decode_balanced_kernel(
 }
 
 // Combine for the token-balanced variant: the pieces of sequence s are the workgroups that overlap its
-// chunk range, at record indices workgroup + s.  One wavefront per (sequence, KV head).
+// chunk range, at record indices workgroup + s.  One wavefront per (sequence, KV head, pair of query heads).
 template <int HD>
 __global__ __launch_bounds__(64) void decode_balanced_combine_kernel(const KParams p)
 {
-    const int kvh = blockIdx.x % p.num_kv_heads;
-    const int s = blockIdx.x / p.num_kv_heads;
+    const int pairs = (p.group + 1) / 2;
+    int bid = blockIdx.x;
+    const int pair = bid % pairs;
+    bid /= pairs;
+    const int kvh = bid % p.num_kv_heads;
+    const int s = bid / p.num_kv_heads;
     const int lane = threadIdx.x;
     const int num_wgs = p.num_splits;
     const int B = p.num_seqs;
@@ -670,23 +669,27 @@ __global__ __launch_bounds__(64) void decode_balanced_combine_kernel(const KPara
     const int w0 = c1 > c0 ? c0 / per_wg : 0;
     const int parts = c1 > c0 ? (c1 - 1) / per_wg - w0 + 1 : 0;
     const int64_t stride = (int64_t)p.num_q_heads * (HD + 2);
-    merge_group<HD>(p, lane, s, kvh, p.workspace + (int64_t)(w0 + s) * stride + (int64_t)kvh * p.group * (HD + 2), parts, HD + 2, stride);
+    merge_pair<HD>(p, lane, s, kvh, pair, p.workspace + (int64_t)(w0 + s) * stride + (int64_t)kvh * p.group * (HD + 2), parts, HD + 2, stride);
 }
 
-// Combine for the fixed-split kernels, one wavefront per (sequence, KV head): records are laid out
+// Combine for the fixed-split kernels, one wavefront per (sequence, KV head, pair of query heads): records are laid out
 // [sequence][head][part].  Parts that hold no key were never written and are not read.
 template <int HD>
 __global__ __launch_bounds__(64) void decode_combine_kernel(const KParams p)
 {
-    const int kvh = blockIdx.x % p.num_kv_heads;
-    const int s = blockIdx.x / p.num_kv_heads;
+    const int pairs = (p.group + 1) / 2;
+    int bid = blockIdx.x;
+    const int pair = bid % pairs;
+    bid /= pairs;
+    const int kvh = bid % p.num_kv_heads;
+    const int s = bid / p.num_kv_heads;
     const int lane = threadIdx.x;
     const int n_kv = p.seq_lens[s];
     int parts = (n_kv + p.split_len - 1) / p.split_len;
     parts = parts < 1 ? 1 : parts;  // part 0 is always written (m = -inf, l = 0 for an empty context)
     const int64_t head_stride = (int64_t)p.num_splits * (HD + 2);
-    merge_group<HD>(p, lane, s, kvh, p.workspace + ((int64_t)s * p.num_q_heads + (int64_t)kvh * p.group) * head_stride, parts,
-                           head_stride, HD + 2);
+    merge_pair<HD>(p, lane, s, kvh, pair, p.workspace + ((int64_t)s * p.num_q_heads + (int64_t)kvh * p.group) * head_stride, parts,
+                          head_stride, HD + 2);
 }
 
 template <int HD, int WAVES>
@@ -729,7 +732,7 @@ hipError_t decode_balanced_launch(const KParams &p, hipStream_t stream)
     hipLaunchKernelGGL((decode_balanced_kernel<HD, WAVES>), dim3((unsigned)blocks), dim3(WAVES * 64), 0, stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(decode_balanced_combine_kernel<HD>, dim3((unsigned)(p.num_seqs * p.num_kv_heads)), dim3(64), 0, stream, p);
+    hipLaunchKernelGGL(decode_balanced_combine_kernel<HD>, dim3((unsigned)(p.num_seqs * p.num_kv_heads * ((p.group + 1) / 2))), dim3(64), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -756,7 +759,7 @@ hipError_t decode_balanced_launch(const KParams &p, hipStream_t stream)
 
 hipError_t launch_decode_combine(const KParams &p, hipStream_t stream)
 {
-    const int64_t blocks = (int64_t)p.num_seqs * p.num_kv_heads;
+    const int64_t blocks = (int64_t)p.num_seqs * p.num_kv_heads * ((p.group + 1) / 2);
     if (blocks <= 0) return hipSuccess;
     if (blocks > 0x7fffffff) return hipErrorInvalidConfiguration;
     if (p.head_dim == 128)
