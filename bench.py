@@ -29,6 +29,23 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
 WORKLOADS = {"c2": 2, "c3": 3, "c4": 4, "c5": 5}
 
+# HBM bytes per call measured with rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE (separate runs, KiB
+# per dispatch summed over the kernels of one call), each scaled by what the same counter reads for a
+# 1 GiB device copy (FETCH_SIZE reads 0.5 KiB per KiB fetched, WRITE_SIZE 1.0); the summary and the
+# commands are in profiles/hbm_traffic_all_workloads_pmc.md.  Keyed by workload and kernel family:
+# a run that selects another family reports null.
+MEASURED_TRAFFIC_BYTES = {
+    ("c2_decode_8b", "decode_bf16_balanced"): (2 * (311776 + 2658) + 4992 + 512) * 1024,
+    ("c5_decode_70b_long", "decode_bf16_balanced"): (2 * (757321 + 4460) + 8700 + 256) * 1024,
+    ("c3_prefill_8b", "prefill_bf16_ring"): (2 * 101256 + 70104) * 1024,
+    ("c4_chunked_prefill", "prefill_bf16_ring seqmajor"): (2 * 213641 + 65536) * 1024,
+}
+
+
+def _traffic(wl_name: str, instance: str):
+    family = instance.split(" ")[0] + (" seqmajor" if instance.endswith("seqmajor") else "")
+    return MEASURED_TRAFFIC_BYTES.get((wl_name, family))
+
 
 def _dev(a):
     import torch
@@ -86,7 +103,9 @@ class Runner:
 
 
 def time_steps(run: Runner, steps: int, warmup: int):
-    """Returns (wall ms per step over the whole timed region, mean ms of per-step HIP event pairs)."""
+    """Returns (ms per step of the timed region, HIP-event ms per step of the same region, median ms of
+    per-step event pairs in eager mode, eager wall ms per step, eager event mean, whether the timed
+    region was a graph replay)."""
     torch = run.torch
     stream = torch.cuda.current_stream()
     sp = stream.cuda_stream
@@ -102,26 +121,54 @@ def time_steps(run: Runner, steps: int, warmup: int):
         run.step(sp)
         b.record(stream)
     torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    eager_ms = (time.perf_counter() - t0) * 1e3 / steps
     per = np.array([a.elapsed_time(b) for a, b in ev])
-    return wall_ms, float(per.mean()), float(np.median(per))
+    # The same K steps as one HIP graph (the paper times its kernels under CUDA/HIP graphs, section
+    # "Method and Investigated Kernels"): the hot calls only enqueue kernels, so they can be captured,
+    # and a replay is free of the host's launch cost.  The graph is replayed once untimed, then timed.
+    graph_ms = None
+    try:
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.graph(g, stream=side):
+            for _ in range(steps):
+                run.step(side.cuda_stream)
+        g.replay()
+        torch.cuda.synchronize()
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        g0.record(stream)
+        g.replay()
+        g1.record(stream)
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / steps
+        graph_ev_ms = g0.elapsed_time(g1) / steps
+        del g
+    except Exception as e:  # keep the eager figure if capture is unavailable
+        print("bench.py: graph timing skipped: %r" % (e,), file=sys.stderr)
+    if graph_ms is None:
+        return eager_ms, float(per.mean()), float(np.median(per)), eager_ms, float(per.mean()), False
+    # under the graph the HIP events bracket all K steps: kernels of a step plus the gap to the next
+    return graph_ms, graph_ev_ms, float(np.median(per)), eager_ms, float(per.mean()), True
 
 
-def _figures(wl, run, wall_ms, ev_mean_ms, ev_med_ms):
+def _figures(wl, run, wall_ms, ev_mean_ms, ev_med_ms, eager_ms, eager_ev_ms, graphed):
     res = {"workload": wl.name, "instance": run.instance, "ms_per_step": wall_ms, "kernel_ms_mean": ev_mean_ms,
-           "kernel_ms_median": ev_med_ms}
+           "kernel_ms_median_eager": ev_med_ms, "kernel_ms_mean_eager": eager_ev_ms, "ms_per_step_eager": eager_ms,
+           "timed_as": "one HIP graph of all steps" if graphed else "eager launches"}
     if wl.kind == "decode":
         nbytes = wl.algorithmic_bytes()
         ach = nbytes / (ev_mean_ms * 1e-3) / 1e9
         res.update(metric="decode_hbm_GBps", unit="GB/s", value=nbytes / (wall_ms * 1e-3) / 1e9, algorithmic_bytes=nbytes,
                    roofline={"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                             "frac": ach / HBM_PEAK_GBPS, "traffic": None})
+                             "frac": ach / HBM_PEAK_GBPS, "traffic": _traffic(wl.name, run.instance)})
     else:
         fl = wl.flops()
         ach = fl / (ev_mean_ms * 1e-3) / 1e12
         res.update(metric="prefill_TFLOPs", unit="TFLOP/s", value=fl / (wall_ms * 1e-3) / 1e12, algorithmic_flops=fl,
                    roofline={"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                             "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None})
+                             "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": _traffic(wl.name, run.instance)})
     return res
 
 
@@ -170,11 +217,16 @@ def cpu_baseline(wl, unit: str):
             nbytes += float(wl.seq_lens[s]) * wl.head_dim * 2 * 2 / (wl.num_q_heads // wl.num_kv_heads)
     seqs, toks, heads = (np.concatenate(x).astype(np.int32) for x in (seqs, toks, heads))
     oracle.attention_rows(prob, seqs[:8], toks[:8], heads[:8])  # load the library, touch the data
-    t0 = time.perf_counter()
-    oracle.attention_rows(prob, seqs, toks, heads)
-    dt = time.perf_counter() - t0
+    # a small workload is over in a fraction of a second: repeat the pass until about 10 s have gone by
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        oracle.attention_rows(prob, seqs, toks, heads)
+        reps += 1
+        if time.perf_counter() - t0 >= 10.0 or reps >= 200:
+            break
+    dt = (time.perf_counter() - t0) / reps
     val = (nbytes / dt / 1e9) if unit == "GB/s" else (flops / dt / 1e12)
-    return {"value": val, "unit": unit, "cores": oracle.num_threads(), "kind": "oracle", "seconds": dt,
+    return {"value": val, "unit": unit, "cores": oracle.num_threads(), "kind": "oracle", "seconds": dt, "passes": reps,
             "sample": "%d output rows (%d whole (sequence, head) pairs, %.2f GFLOP of the workload's %.2f) of %s" % (
                 len(seqs), len(np.unique(seqs * 1000 + heads)), flops / 1e9, wl.flops() / 1e9, wl.name)}
 
@@ -182,7 +234,7 @@ def cpu_baseline(wl, unit: str):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", choices=sorted(WORKLOADS), default="c2")
     ap.add_argument("--no-extra", action="store_true", help="skip the other configurations")
@@ -217,7 +269,8 @@ def main():
         "config": {"workload": wl.name, "instance": main_res["instance"], "num_seqs": wl.num_seqs,
                    "num_q_heads": wl.num_q_heads, "num_kv_heads": wl.num_kv_heads, "head_dim": wl.head_dim,
                    "kv_block_size": wl.block_size, "kv_tokens": int(wl.seq_lens.sum()), "tuned": not a.no_tune},
-        "kernel_ms_mean": main_res["kernel_ms_mean"], "kernel_ms_median": main_res["kernel_ms_median"],
+        "kernel_ms_mean": main_res["kernel_ms_mean"], "kernel_ms_mean_eager": main_res["kernel_ms_mean_eager"],
+        "ms_per_step_eager": main_res["ms_per_step_eager"], "timed_as": main_res["timed_as"],
         "roofline": main_res["roofline"], "untuned": main_res["untuned"],
     }
     if not a.no_cpu:
@@ -230,7 +283,8 @@ def main():
                 continue
             torch.cuda.empty_cache()
             _, r = measure(wid, max(5, a.steps // 2), max(2, a.warmup // 2), not a.no_tune)
-            extra[name] = {k: r[k] for k in ("workload", "instance", "metric", "value", "unit", "ms_per_step", "kernel_ms_mean", "roofline", "untuned")}
+            extra[name] = {k: r[k] for k in ("workload", "instance", "metric", "value", "unit", "ms_per_step", "ms_per_step_eager", "timed_as",
+                                             "kernel_ms_mean", "roofline", "untuned")}
         line["extra"] = extra
     print(json.dumps(line), flush=True)
 

@@ -132,15 +132,25 @@ size_t attn_workspace_bytes(const attn_args *args, int is_decode);
  * prefill) query_start_loc are used, if not NULL: the tuning batch then has the
  * caller's own lengths (copied to the host; they must respect max_q_len and
  * max_kv_len).  Otherwise lengths are spread evenly between half of and the full
- * max_q_len / max_kv_len.  The call records the fastest instance and, if
- * cache_path is not NULL, merges it into that file (atomic replace).  `iters`
- * timed launches per instance (<= 0: a default).  Synchronous; not capturable.
- * flags: bit 0 = print one line per instance to stderr.
+ * max_q_len / max_kv_len.  The search is a successive halving: three timed
+ * launches of every valid instance, iters/2 of the best third (the built-in
+ * choice and the winners already known for neighbouring buckets always stay in),
+ * `iters` (<= 0: a default) of the best three; an instance three times slower
+ * than the best so far is dropped after one launch.  The call records the
+ * fastest instance and, if cache_path is not NULL, merges it into that file
+ * (atomic replace).  Synchronous; not capturable.
+ * flags: bit 0 = print one line per measurement to stderr; bit 1 = exhaustive
+ * sweep (`iters` launches of every valid instance) instead of the halving.
  */
 int attn_tune(const attn_args *shape_like, int is_decode, const char *cache_path, int iters, int flags);
 
+/* Writes the NUL-terminated environment key that attn_tune stores with every cache line (device
+ * architecture, compute units, HIP runtime and driver versions, a hash of the compiled instance set)
+ * and returns its length.  Pure host function apart from a device-property query. */
+int attn_environment_key(char *buf, size_t buf_bytes);
+
 /* Load winners from a cache file written by attn_tune.  Entries recorded for a different device,
- * CU count or library build are skipped.  Also done lazily from $ATTN_TUNE_CACHE on the first hot
+ * CU count, runtime or library build are skipped.  Also done lazily from $ATTN_TUNE_CACHE on the first hot
  * call.  A missing or corrupt file returns ATTN_ERR_CACHE_IO and leaves the built-in heuristic in
  * force; hot calls never fail because of the cache. */
 int attn_load_cache(const char *cache_path);

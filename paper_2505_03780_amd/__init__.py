@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     AttnError,
     attn_clear_cache,
     attn_decode_paged,
+    attn_environment_key,
     attn_force_instance,
     attn_instance_name,
     attn_load_cache,

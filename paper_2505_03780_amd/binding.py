@@ -82,6 +82,8 @@ def load_library():
     lib.attn_workspace_bytes.argtypes = [P, ctypes.c_int]
     lib.attn_tune.restype = ctypes.c_int
     lib.attn_tune.argtypes = [P, ctypes.c_int, ctypes.c_char_p, ctypes.c_int, ctypes.c_int]
+    lib.attn_environment_key.restype = ctypes.c_int
+    lib.attn_environment_key.argtypes = [ctypes.c_char_p, ctypes.c_size_t]
     lib.attn_load_cache.restype = ctypes.c_int
     lib.attn_load_cache.argtypes = [ctypes.c_char_p]
     lib.attn_clear_cache.restype = None
@@ -205,6 +207,12 @@ def attn_tune(args: AttnArgs, is_decode: bool, cache_path: Optional[str] = None,
     rc = load_library().attn_tune(ctypes.byref(args), 1 if is_decode else 0, path, int(iters), int(flags))
     if rc != 0:
         raise AttnError(rc, "attn_tune")
+
+
+def attn_environment_key() -> str:
+    buf = ctypes.create_string_buffer(256)
+    load_library().attn_environment_key(buf, len(buf))
+    return buf.value.decode()
 
 
 def attn_load_cache(cache_path: str) -> int:

@@ -35,7 +35,9 @@ namespace {
 
 constexpr const char *kCacheMagic = "attn-tune-cache-v1";
 // Changes whenever the kernels change in a way that invalidates old timings.
-constexpr const char *kBuildId = "k1";
+// Identifies the set of compiled instances: a cache line tuned against another set must not be
+// trusted (the paper asks that cached results record the environment they were measured in).
+std::string build_id();
 constexpr int kMinSplitLen = 128;
 
 std::mutex g_mu;
@@ -143,6 +145,22 @@ std::string bucket_key(const KParams &p, int dtype, int is_decode)
     return buf;
 }
 
+// Keys of the buckets next to the one of `p`: one step up or down in each of the three extents.
+std::vector<std::string> neighbour_keys(const KParams &p, int dtype, int is_decode)
+{
+    std::vector<std::string> out;
+    for (int axis = 0; axis < 3; ++axis)
+        for (int dir = -1; dir <= 1; dir += 2) {
+            KParams q = p;
+            int *ext = axis == 0 ? &q.num_seqs : axis == 1 ? &q.max_q_len : &q.max_kv_len;
+            const int e = ilog2_ceil(std::max(1, *ext)) + dir;
+            if (e < 0 || e > 30 || (axis == 1 && is_decode)) continue;
+            *ext = 1 << e;
+            out.push_back(bucket_key(q, dtype, is_decode));
+        }
+    return out;
+}
+
 constexpr int kMaxBalancedWgs = 2048;  // workspace bound for the token-balanced decode
 
 int compute_units()
@@ -238,13 +256,29 @@ std::string environment_key()
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
         (void)hipGetLastError();
-        return std::string("nodevice|cu0|") + kBuildId;
+        return std::string("nodevice|cu0|") + build_id();
     }
-    int rt = 0;
+    int rt = 0, drv = 0;
     (void)hipRuntimeGetVersion(&rt);
+    (void)hipDriverGetVersion(&drv);
     std::ostringstream os;
-    os << prop.gcnArchName << "|cu" << prop.multiProcessorCount << "|hip" << rt << "|" << kBuildId;
+    os << prop.gcnArchName << "|cu" << prop.multiProcessorCount << "|hip" << rt << "|drv" << drv << "|" << build_id();
     return os.str();
+}
+
+std::string build_id()
+{
+    // FNV-1a over the names of all instances, in table order
+    uint64_t h = 1469598103934665603ull;
+    for (int is_decode = 0; is_decode < 2; ++is_decode) {
+        int n;
+        const Instance *t = instances(is_decode, &n);
+        for (int i = 0; i < n; ++i)
+            for (const char *c = t[i].name; *c; ++c) h = (h ^ (unsigned char)*c) * 1099511628211ull;
+    }
+    char buf[24];
+    snprintf(buf, sizeof buf, "k%016llx", (unsigned long long)h);
+    return buf;
 }
 
 int instance_by_name(int is_decode, const std::string &name)
@@ -520,32 +554,84 @@ int tune(const attn_args *shape, int is_decode, const char *cache_path, int iter
     const Instance *t = instances(is_decode, &n);
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return ATTN_ERR_HIP;
-    int best = -1;
-    double best_us = 0;
-    for (int id = 0; id < n; ++id) {
-        if (!t[id].valid(p)) continue;
-        bool fail = false;
-        for (int w = 0; w < 2 && !fail; ++w) fail = run(&a, is_decode, 0, id) != ATTN_OK;
-        if (fail || hipDeviceSynchronize() != hipSuccess) {
+    // median of `count` timed launches after `warm` untimed ones; < 0 if the instance fails.  A launch
+    // slower than `give_up_us` ends the measurement early (the instance cannot win any more).
+    auto time_instance = [&](int id, int warm, int count, double give_up_us) -> double {
+        for (int w = 0; w < warm; ++w)
+            if (run(&a, is_decode, 0, id) != ATTN_OK) return -1.0;
+        if (hipDeviceSynchronize() != hipSuccess) {
             (void)hipGetLastError();
-            continue;
+            return -1.0;
         }
-        std::vector<float> ms(iters);
-        for (int i = 0; i < iters && !fail; ++i) {
+        std::vector<float> ms;
+        for (int i = 0; i < count; ++i) {
             (void)hipEventRecord(e0, 0);
-            fail = run(&a, is_decode, 0, id) != ATTN_OK;
+            if (run(&a, is_decode, 0, id) != ATTN_OK) return -1.0;
             (void)hipEventRecord(e1, 0);
-            if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms[i], e0, e1) != hipSuccess) fail = true;
+            float t = 0.f;
+            if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&t, e0, e1) != hipSuccess) {
+                (void)hipGetLastError();
+                return -1.0;
+            }
+            ms.push_back(t);
+            if (1000.0 * t > give_up_us) break;
         }
-        if (fail) continue;
         std::sort(ms.begin(), ms.end());
-        const double us = 1000.0 * ms[iters / 2];
-        if (flags & 1) fprintf(stderr, "[attn_tune] %s :: %-40s %10.2f us\n", key.c_str(), t[id].name, us);
-        if (best < 0 || us < best_us) {
-            best = id;
-            best_us = us;
+        return 1000.0 * ms[ms.size() / 2];
+    };
+    struct Cand {
+        int id;
+        double us;
+        bool seed;
+    };
+    std::vector<Cand> cand;
+    for (int id = 0; id < n; ++id)
+        if (t[id].valid(p)) cand.push_back(Cand{id, 0.0, false});
+    if (cand.empty()) return ATTN_ERR_UNSUPPORTED;
+    // seeds always survive the first cut: the built-in choice and the winners of the neighbouring buckets
+    {
+        std::vector<int> seeds;
+        const int h = heuristic(p, is_decode);
+        if (h >= 0) seeds.push_back(h);
+        std::lock_guard<std::mutex> lk(g_mu);
+        for (const std::string &nk : neighbour_keys(p, a.dtype, is_decode)) {
+            auto it = g_winner[is_decode].find(nk);
+            if (it != g_winner[is_decode].end()) seeds.push_back(it->second);
+        }
+        for (Cand &c : cand)
+            for (int sd : seeds) c.seed |= c.id == sd;
+    }
+    const bool exhaustive = (flags & 2) != 0;
+    // Successive halving: a cheap look at every valid instance, a closer one at the best third, the
+    // full count only for the last three.  (Exhaustive sweeps are what the paper names as the cost
+    // that keeps autotuning out of practice: its requirement list asks for an efficient search.)
+    const int plan[3][2] = {{3, 0}, {std::max(5, iters / 2), 0}, {iters, 0}};
+    const int rounds = exhaustive ? 1 : 3;
+    int launches = 0;
+    for (int r = 0; r < rounds; ++r) {
+        const int count = exhaustive ? iters : plan[r][0];
+        double best_so_far = 1e30;
+        for (Cand &c : cand) {
+            c.us = time_instance(c.id, r == 0 ? 2 : 1, count, exhaustive ? 1e30 : 3.0 * best_so_far);
+            launches += count + (r == 0 ? 2 : 1);
+            if (c.us >= 0 && c.us < best_so_far) best_so_far = c.us;
+            if ((flags & 1) && c.us >= 0)
+                fprintf(stderr, "[attn_tune] %s :: round %d %-48s %10.2f us\n", key.c_str(), r, t[c.id].name, c.us);
+        }
+        cand.erase(std::remove_if(cand.begin(), cand.end(), [](const Cand &c) { return c.us < 0; }), cand.end());
+        if (cand.empty()) break;
+        std::stable_sort(cand.begin(), cand.end(), [](const Cand &x, const Cand &y) { return x.us < y.us; });
+        if (r + 1 < rounds) {
+            const size_t keep = r == 0 ? std::max<size_t>(4, (cand.size() + 2) / 3) : 3;
+            std::vector<Cand> next;
+            for (size_t i = 0; i < cand.size(); ++i)
+                if (i < keep || (r == 0 && cand[i].seed)) next.push_back(cand[i]);
+            cand.swap(next);
         }
     }
+    int best = cand.empty() ? -1 : cand[0].id;
+    double best_us = cand.empty() ? 0.0 : cand[0].us;
+    if (flags & 1) fprintf(stderr, "[attn_tune] %s :: %d launches in all\n", key.c_str(), launches);
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     if (best < 0) return ATTN_ERR_UNSUPPORTED;
@@ -620,6 +706,13 @@ size_t attn_workspace_bytes(const attn_args *a, int is_decode)
 int attn_tune(const attn_args *shape_like, int is_decode, const char *cache_path, int iters, int flags)
 {
     return tune(shape_like, is_decode ? 1 : 0, cache_path, iters, flags);
+}
+
+int attn_environment_key(char *buf, size_t buf_bytes)
+{
+    const std::string k = environment_key();
+    if (buf && buf_bytes) snprintf(buf, buf_bytes, "%s", k.c_str());
+    return (int)k.size();
 }
 
 int attn_load_cache(const char *cache_path)

@@ -69,3 +69,22 @@ def test_tune_writes_cache_and_hot_calls_use_the_winner(tmp_path, kind):
     A.attn_clear_cache()
     assert A.attn_load_cache(str(stale)) == 0
     assert A.attn_selected_instance(args, is_decode) == default
+
+
+def test_exhaustive_sweep_flag_and_environment_key(tmp_path):
+    wl = W.make_paged(73, "decode", np.ones(4, np.int32), [700, 333, 1024, 90], 32, 8, 128, 16, 300)
+    dw = DeviceWorkload(wl)
+    args = dw.args(True)
+    cache = str(tmp_path / "tune.txt")
+    A.attn_tune(args, True, cache, iters=2, flags=2)  # every valid instance, two launches each
+    rows = _cache_lines(cache)
+    assert len(rows) == 1 and rows[0][0] == A.attn_environment_key()
+    assert rows[0][0].startswith("gfx950") and "|hip" in rows[0][0] and "|drv" in rows[0][0]
+    ref = oracle.attention(oracle_problem(wl))
+    assert_close(to_host_f64(dw.run(True)), ref, "bf16", "after exhaustive tune: " + rows[0][2])
+    # the halving search seeded by this winner (a neighbouring bucket) still ends on a valid instance
+    wider = A.make_args(dw.q, dw.k, dw.v, dw.out, dw.seq_lens, wl.scale, max_q_len=1, max_kv_len=2 * dw.max_kv,
+                        block_table=dw.bt, is_decode=True)
+    A.attn_tune(wider, True, cache, iters=4, flags=0)
+    assert len(_cache_lines(cache)) == 2
+    assert_close(to_host_f64(dw.run(True)), ref, "bf16", "after seeded tune")

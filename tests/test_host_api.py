@@ -136,10 +136,10 @@ def test_cache_file_round_trip_stale_and_corrupt(tmp_path):
     default = A.attn_selected_instance(_args(), False)
     other = next(i for i, n in enumerate(names_p) if "d128" in n and "hpw1" in n and i != default)
     key = "prefill|bf16|d128|hq32|hkv8|contig|bs0|c1|B2|q7|kv7"
-    env_here = "nodevice|cu0|k1"  # what the library reports in a process without a GPU
+    env_here = A.attn_environment_key()
     import torch
-    if torch.cuda.is_available():
-        pytest.skip("environment key differs on a GPU box; covered by the GPU tuner test")
+    if not torch.cuda.is_available():  # what the library reports in a process without a GPU
+        assert re.fullmatch(r"nodevice\|cu0\|k[0-9a-f]{16}", env_here), env_here
     good = tmp_path / "cache.txt"
     good.write_text("attn-tune-cache-v1\n%s\t%s\t%s\t12.5\n" % (env_here, key, names_p[other]))
     assert A.attn_load_cache(str(good)) == 0
