@@ -1,4 +1,4 @@
-"""fp64 CPU oracle for fused attention.  TEST INFRASTRUCTURE ONLY.
+"""fp64 CPU oracles for fused attention and the fused RMS layer norm.  TEST INFRASTRUCTURE ONLY.
 
 Only tests, ``__graft_entry__.smoke()`` and ``bench.py``'s cpu_baseline leg may
 import this package; the product library never does.
@@ -10,3 +10,4 @@ from .attn_oracle import (  # noqa: F401
     build,
     num_threads,
 )
+from .rmsnorm_oracle import rms_norm  # noqa: F401

@@ -29,6 +29,7 @@
 
 #include "../../include/attn.h"
 #include "kernel_params.hpp"
+#include "tuner_cache.hpp"
 
 namespace attn {
 namespace {
@@ -42,6 +43,7 @@ constexpr int kMinSplitLen = 128;
 
 std::mutex g_mu;
 std::unordered_map<std::string, int> g_winner[2];  // [is_decode]: bucket key -> instance id
+std::unordered_map<std::string, std::string> g_named;  // other kernel kinds: bucket key -> instance name
 std::atomic<int> g_forced[2] = {{-1}, {-1}};
 bool g_env_cache_tried = false;
 
@@ -250,7 +252,7 @@ int heuristic(const KParams &p, int is_decode)
 }
 
 // ---- environment key and cache file ------------------------------------------------------------
-std::string environment_key()
+std::string env_key_impl()
 {
     hipDeviceProp_t prop;
     int dev = 0;
@@ -334,10 +336,14 @@ int load_cache_locked(const char *path)
     std::vector<CacheLine> lines;
     int rc = read_cache_file(path, &lines);
     if (rc != ATTN_OK) return rc;
-    const std::string env = environment_key();
+    const std::string env = env_key_impl();
     for (const CacheLine &cl : lines) {
         if (cl.env != env) continue;  // measured on another device or library build
         const int is_decode = cl.key.compare(0, 6, "decode") == 0;
+        if (!is_decode && cl.key.compare(0, 7, "prefill") != 0) {
+            g_named[cl.key] = cl.inst;
+            continue;
+        }
         const int id = instance_by_name(is_decode, cl.inst);
         if (id < 0) continue;
         g_winner[is_decode][cl.key] = id;
@@ -642,15 +648,24 @@ int tune(const attn_args *shape, int is_decode, const char *cache_path, int iter
     if (flags & 1) fprintf(stderr, "[attn_tune] winner %s -> %s (%.2f us)\n", key.c_str(), t[best].name, best_us);
     if (!cache_path) return ATTN_OK;
 
-    // merge into the file: keep every other line, replace this (environment, bucket) pair
+    return merge_cache_line(cache_path, key, t[best].name, best_us);
+}
+
+}  // namespace
+
+std::string environment_key() { return env_key_impl(); }
+
+int merge_cache_line(const char *path, const std::string &key, const std::string &instance_name, double us)
+{
+    // keep every other line, replace this (environment, bucket) pair
     std::vector<CacheLine> lines;
-    (void)read_cache_file(cache_path, &lines);  // a missing or damaged file is simply rewritten
-    const std::string env = environment_key();
+    (void)read_cache_file(path, &lines);  // a missing or damaged file is simply rewritten
+    const std::string env = env_key_impl();
     std::vector<CacheLine> keep;
     for (const CacheLine &cl : lines)
         if (!(cl.env == env && cl.key == key)) keep.push_back(cl);
-    keep.push_back(CacheLine{env, key, t[best].name, best_us});
-    const std::string tmp = std::string(cache_path) + ".tmp." + std::to_string((long)getpid());
+    keep.push_back(CacheLine{env, key, instance_name, us});
+    const std::string tmp = std::string(path) + ".tmp." + std::to_string((long)getpid());
     {
         std::ofstream out(tmp, std::ios::trunc);
         if (!out) return ATTN_ERR_CACHE_IO;
@@ -662,14 +677,29 @@ int tune(const attn_args *shape, int is_decode, const char *cache_path, int iter
             return ATTN_ERR_CACHE_IO;
         }
     }
-    if (rename(tmp.c_str(), cache_path) != 0) {
+    if (rename(tmp.c_str(), path) != 0) {
         (void)remove(tmp.c_str());
         return ATTN_ERR_CACHE_IO;
     }
     return ATTN_OK;
 }
 
-}  // namespace
+void store_named_winner(const std::string &key, const std::string &instance_name)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_named[key] = instance_name;
+}
+
+bool lookup_named_winner(const std::string &key, std::string *instance_name)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    auto it = g_named.find(key);
+    if (it == g_named.end()) return false;
+    *instance_name = it->second;
+    return true;
+}
+
+void load_env_cache_once() { maybe_load_env_cache(); }
 
 const Instance *prefill_instances(int *count)
 {
@@ -710,7 +740,7 @@ int attn_tune(const attn_args *shape_like, int is_decode, const char *cache_path
 
 int attn_environment_key(char *buf, size_t buf_bytes)
 {
-    const std::string k = environment_key();
+    const std::string k = env_key_impl();
     if (buf && buf_bytes) snprintf(buf, buf_bytes, "%s", k.c_str());
     return (int)k.size();
 }
@@ -727,6 +757,7 @@ void attn_clear_cache(void)
     std::lock_guard<std::mutex> lk(g_mu);
     g_winner[0].clear();
     g_winner[1].clear();
+    g_named.clear();
 }
 
 int attn_num_instances(int is_decode)
