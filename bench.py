@@ -191,6 +191,59 @@ def measure(wl_id: int, steps: int, warmup: int, tune: bool):
     return wl, res
 
 
+def measure_rmsnorm(steps: int, warmup: int, tune: bool):
+    """The paper's second kernel, fused residual add + RMS norm at the 8B model's hidden size over a
+    prefill-sized batch of tokens: HBM-bound, reported as algorithmic GB/s."""
+    import torch
+
+    import paper_2505_03780_amd as A
+    import workloads as W
+
+    wl = W.rmsnorm_8b_prefill()
+    x, res, w = _dev(wl.x), _dev(wl.residual), _dev(wl.weight)
+    # two sets of buffers take turns, so that a step never finds its rows in the last-level cache
+    sets = [(x, res, torch.empty_like(x)), (x.clone(), res.clone(), torch.empty_like(x))]
+    args = [A.make_rmsnorm_args(a, w, o, wl.eps, r) for a, r, o in sets]
+    lib = A.load_library()
+    stream = torch.cuda.current_stream()
+    import ctypes
+
+    def loop(n, sp):
+        for i in range(n):
+            rc = lib.rmsnorm_fused_add(ctypes.byref(args[i % 2]), sp)
+            if rc != 0:
+                raise RuntimeError("rmsnorm_fused_add failed: %d" % rc)
+
+    untuned = A.rmsnorm_instance_name(A.rmsnorm_selected_instance(args[0]))
+    if tune:
+        A.rmsnorm_tune(args[0], os.environ.get("ATTN_TUNE_CACHE"), 10, 0)
+    inst = A.rmsnorm_instance_name(A.rmsnorm_selected_instance(args[0]))
+    loop(warmup, stream.cuda_stream)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(stream)
+    with torch.cuda.graph(g, stream=side):
+        loop(steps, side.cuda_stream)
+    g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    g.replay()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    ev_ms = e0.elapsed_time(e1) / steps
+    nbytes = wl.algorithmic_bytes()
+    ach = nbytes / (ev_ms * 1e-3) / 1e9
+    return {"workload": wl.name, "instance": inst, "untuned_instance": untuned, "metric": "rmsnorm_hbm_GBps", "unit": "GB/s",
+            "value": nbytes / (wall_ms * 1e-3) / 1e9, "ms_per_step": wall_ms, "kernel_ms_mean": ev_ms, "algorithmic_bytes": nbytes,
+            "timed_as": "one HIP graph of all steps",
+            "roofline": {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBPS,
+                         "traffic": None}}
+
+
 def cpu_baseline(wl, unit: str):
     """The fp64 oracle, as it stands, on a bounded sample of the same workload (about 10-30 s of CPU)."""
     import oracle
@@ -285,6 +338,8 @@ def main():
             _, r = measure(wid, max(5, a.steps // 2), max(2, a.warmup // 2), not a.no_tune)
             extra[name] = {k: r[k] for k in ("workload", "instance", "metric", "value", "unit", "ms_per_step", "ms_per_step_eager", "timed_as",
                                              "kernel_ms_mean", "roofline", "untuned")}
+        torch.cuda.empty_cache()
+        extra["rmsnorm"] = measure_rmsnorm(a.steps, a.warmup, not a.no_tune)
         line["extra"] = extra
     print(json.dumps(line), flush=True)
 

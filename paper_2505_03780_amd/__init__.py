@@ -23,4 +23,12 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     make_args,
+    RmsNormArgs,
+    make_rmsnorm_args,
+    rmsnorm_force_instance,
+    rmsnorm_fused_add,
+    rmsnorm_instance_name,
+    rmsnorm_num_instances,
+    rmsnorm_selected_instance,
+    rmsnorm_tune,
 )

@@ -98,8 +98,39 @@ def load_library():
     lib.attn_force_instance.argtypes = [ctypes.c_int, ctypes.c_int]
     lib.attn_status_string.restype = ctypes.c_char_p
     lib.attn_status_string.argtypes = [ctypes.c_int]
+    R = ctypes.POINTER(RmsNormArgs)
+    lib.rmsnorm_fused_add.restype = ctypes.c_int
+    lib.rmsnorm_fused_add.argtypes = [R, ctypes.c_void_p]
+    lib.rmsnorm_tune.restype = ctypes.c_int
+    lib.rmsnorm_tune.argtypes = [R, ctypes.c_char_p, ctypes.c_int, ctypes.c_int]
+    lib.rmsnorm_num_instances.restype = ctypes.c_int
+    lib.rmsnorm_num_instances.argtypes = []
+    lib.rmsnorm_instance_name.restype = ctypes.c_int
+    lib.rmsnorm_instance_name.argtypes = [ctypes.c_int, ctypes.c_char_p, ctypes.c_size_t]
+    lib.rmsnorm_selected_instance.restype = ctypes.c_int
+    lib.rmsnorm_selected_instance.argtypes = [R]
+    lib.rmsnorm_force_instance.restype = None
+    lib.rmsnorm_force_instance.argtypes = [ctypes.c_int]
     _lib = lib
     return lib
+
+
+class RmsNormArgs(ctypes.Structure):
+    """Mirror of ``rmsnorm_args`` in include/rmsnorm.h."""
+    _fields_ = [
+        ("struct_bytes", ctypes.c_uint32),
+        ("dtype", ctypes.c_int32),
+        ("num_tokens", ctypes.c_int32),
+        ("hidden", ctypes.c_int32),
+        ("x", ctypes.c_void_p),
+        ("x_stride", ctypes.c_int64),
+        ("residual", ctypes.c_void_p),
+        ("residual_stride", ctypes.c_int64),
+        ("weight", ctypes.c_void_p),
+        ("out", ctypes.c_void_p),
+        ("out_stride", ctypes.c_int64),
+        ("eps", ctypes.c_float),
+    ]
 
 
 def attn_status_string(status: int) -> str:
@@ -241,3 +272,57 @@ def attn_selected_instance(args: AttnArgs, is_decode: bool) -> int:
 
 def attn_force_instance(is_decode: bool, idx: int) -> None:
     load_library().attn_force_instance(1 if is_decode else 0, int(idx))
+
+
+# ---- fused RMS layer norm (include/rmsnorm.h) ------------------------------------------------------
+
+def make_rmsnorm_args(x, weight, out, eps, residual=None) -> RmsNormArgs:
+    """x, out, residual: [T, H] device tensors with a contiguous last dimension; weight: [H]."""
+    for name, t in (("x", x), ("out", out), ("residual", residual), ("weight", weight)):
+        if t is not None and t.stride(-1) != 1:
+            raise ValueError("%s: the hidden dimension must be contiguous" % name)
+    a = RmsNormArgs()
+    a.struct_bytes = ctypes.sizeof(RmsNormArgs)
+    a.dtype = _dtype_code(x)
+    a.num_tokens, a.hidden = int(x.shape[0]), int(x.shape[1])
+    a.x, a.x_stride = _ptr(x), x.stride(0)
+    a.residual, a.residual_stride = _ptr(residual), (0 if residual is None else residual.stride(0))
+    a.weight = _ptr(weight)
+    a.out, a.out_stride = _ptr(out), out.stride(0)
+    a.eps = float(eps)
+    return a
+
+
+def rmsnorm_fused_add(x, weight, out, eps, residual=None, stream=None, args: Optional[RmsNormArgs] = None) -> None:
+    """Enqueue out = rmsnorm(x + residual) * weight and residual <- x + residual (residual optional)."""
+    a = args or make_rmsnorm_args(x, weight, out, eps, residual)
+    rc = load_library().rmsnorm_fused_add(ctypes.byref(a), _stream_ptr(stream))
+    if rc != 0:
+        raise AttnError(rc, "rmsnorm_fused_add")
+
+
+def rmsnorm_tune(args: RmsNormArgs, cache_path: Optional[str] = None, iters: int = 20, flags: int = 0) -> None:
+    path = None if cache_path is None else os.fsencode(cache_path)
+    rc = load_library().rmsnorm_tune(ctypes.byref(args), path, int(iters), int(flags))
+    if rc != 0:
+        raise AttnError(rc, "rmsnorm_tune")
+
+
+def rmsnorm_num_instances() -> int:
+    return int(load_library().rmsnorm_num_instances())
+
+
+def rmsnorm_instance_name(idx: int) -> str:
+    buf = ctypes.create_string_buffer(128)
+    n = load_library().rmsnorm_instance_name(int(idx), buf, len(buf))
+    if n < 0:
+        raise AttnError(n, "rmsnorm_instance_name")
+    return buf.value.decode()
+
+
+def rmsnorm_selected_instance(args: RmsNormArgs) -> int:
+    return int(load_library().rmsnorm_selected_instance(ctypes.byref(args)))
+
+
+def rmsnorm_force_instance(idx: int) -> None:
+    load_library().rmsnorm_force_instance(int(idx))

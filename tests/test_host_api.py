@@ -34,10 +34,12 @@ def _paged(**kw):
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "attn.h")).read()
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    names = set(re.findall(r"\b(attn_[a-z_]+)\s*\(", header))
-    assert {"attn_prefill_varlen", "attn_decode_paged", "attn_tune", "attn_workspace_bytes"} <= names
+    names = set()
+    for h in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        header = open(os.path.join(ROOT, "include", h)).read()
+        header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+        names |= set(re.findall(r"\b((?:attn|rmsnorm)_[a-z_]+)\s*\(", header))
+    assert {"attn_prefill_varlen", "attn_decode_paged", "attn_tune", "attn_workspace_bytes", "rmsnorm_fused_add", "rmsnorm_tune"} <= names
     lib = A.load_library()
     for n in sorted(names):
         assert hasattr(lib, n), "missing export " + n
@@ -174,3 +176,42 @@ def test_tune_rejects_bad_requests_before_touching_the_device():
     assert lib.attn_tune(_args(dtype=A.ATTN_F32), 0, None, 1, 0) == -3
     assert lib.attn_tune(_args(head_dim=80), 0, None, 1, 0) == -4
     assert lib.attn_tune(_args(num_kv_heads=5), 0, None, 1, 0) == -2
+
+
+def _rms(**kw):
+    a = A.RmsNormArgs()
+    a.struct_bytes = ctypes.sizeof(A.RmsNormArgs)
+    a.dtype, a.num_tokens, a.hidden = A.ATTN_BF16, 128, 4096
+    a.x, a.weight, a.out, a.residual = 0x10000, 0x20000, 0x30000, 0x40000
+    a.x_stride = a.out_stride = a.residual_stride = 4096
+    a.eps = 1e-5
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return a
+
+
+def test_rmsnorm_validation_and_selection_on_the_host():
+    lib = A.load_library()
+    assert ctypes.sizeof(A.RmsNormArgs) == 80
+    assert lib.rmsnorm_fused_add(None, None) == -1
+    assert lib.rmsnorm_fused_add(_rms(struct_bytes=8), None) == -2
+    assert lib.rmsnorm_fused_add(_rms(dtype=A.ATTN_F32), None) == -3
+    assert lib.rmsnorm_fused_add(_rms(hidden=4100), None) == -4
+    assert lib.rmsnorm_fused_add(_rms(hidden=32768, x_stride=32768, out_stride=32768, residual_stride=32768), None) == -4
+    assert lib.rmsnorm_fused_add(_rms(x=None), None) == -1
+    assert lib.rmsnorm_fused_add(_rms(x_stride=4000), None) == -2
+    assert lib.rmsnorm_fused_add(_rms(out=0x30008), None) == -2  # not 16-byte aligned
+    assert lib.rmsnorm_fused_add(_rms(num_tokens=0, x=None, out=None), None) == 0  # nothing to do
+    names = [A.rmsnorm_instance_name(i) for i in range(A.rmsnorm_num_instances())]
+    assert len(set(names)) == len(names) >= 10
+    # many rows: one wavefront per row; few rows: more lanes per row
+    assert "tpr64 " in names[A.rmsnorm_selected_instance(_rms(num_tokens=8192))]
+    assert "tpr512 " in names[A.rmsnorm_selected_instance(_rms(num_tokens=16))]
+    # every supported hidden size has at least one instance; a forced one that does not fit is refused
+    for h in range(8, 16385, 8):
+        assert A.rmsnorm_selected_instance(_rms(hidden=h, x_stride=h, out_stride=h, residual_stride=h)) >= 0, h
+    A.rmsnorm_force_instance(names.index("rmsnorm_bf16 tpr64 vpt2 rows4"))
+    assert A.rmsnorm_selected_instance(_rms()) == -4
+    A.rmsnorm_force_instance(-1)
+    assert lib.rmsnorm_tune(None, None, 1, 0) == -1
+    assert lib.rmsnorm_tune(_rms(hidden=12), None, 1, 0) == -4

@@ -234,3 +234,47 @@ def scatter_to_pool(k_contig, v_contig, kv_start_loc, seq_lens, block_table, blo
             kp[blk, :cnt] = k_contig[base + j0 : base + j0 + cnt]
             vp[blk, :cnt] = v_contig[base + j0 : base + j0 + cnt]
     return kp, vp
+
+
+# --- fused RMS layer norm (the paper's second kernel) ----------------------------------------------
+
+@dataclass
+class RmsNormWorkload:
+    """Seeded inputs of one fused (residual add +) RMS norm call; arrays are bf16 bit patterns."""
+    name: str
+    x: np.ndarray                  # [T, H] uint16
+    residual: Optional[np.ndarray]  # [T, H] uint16 or None
+    weight: np.ndarray             # [H] uint16
+    eps: float
+
+    @property
+    def num_tokens(self) -> int:
+        return int(self.x.shape[0])
+
+    @property
+    def hidden(self) -> int:
+        return int(self.x.shape[1])
+
+    def algorithmic_bytes(self) -> int:
+        """Every row read once and written once per tensor, plus the weight once."""
+        rows = 2 * self.x.size * 2 + (2 * self.x.size * 2 if self.residual is not None else 0)
+        return int(rows + self.weight.size * 2)
+
+
+def make_rmsnorm(seed: int, num_tokens: int, hidden: int, with_residual: bool = True, eps: float = 1e-5,
+                 name: str = "rmsnorm") -> RmsNormWorkload:
+    """Activations N(0,1), a residual stream of larger spread N(0, 2^2), weights 1 + 0.1 N(0,1), all
+    rounded to bf16: the shape of a transformer layer's input norm (hidden 4096 for the 8B model of
+    the paper's study, 8192 for the 70B one)."""
+    rng = np.random.default_rng(seed)
+    x = _normal_bf16(rng, (num_tokens, hidden))
+    res = None
+    if with_residual:
+        res = f32_to_bf16_bits(2.0 * rng.standard_normal((num_tokens, hidden), dtype=np.float32))
+    w = f32_to_bf16_bits(1.0 + 0.1 * rng.standard_normal(hidden, dtype=np.float32))
+    return RmsNormWorkload(name, x, res, w, eps)
+
+
+def rmsnorm_8b_prefill(seed: int = 11) -> RmsNormWorkload:
+    """8192 tokens (a prefill batch like configuration 3) x hidden 4096."""
+    return make_rmsnorm(seed, 8192, 4096, True, 1e-5, "rmsnorm_8b_t8192_h4096")
