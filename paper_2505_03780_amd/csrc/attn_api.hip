@@ -223,18 +223,26 @@ int heuristic(const KParams &p, int is_decode)
     if (!is_decode) {
         // pack as many heads of a KV head as divide the group: they share every K/V tile
         int hpw = p.group % 4 == 0 ? 4 : (p.group % 2 == 0 ? 2 : 1);
-        // a cached prefix that dominates the key range is streamed once per query tile: run the tiles of
-        // a sequence side by side so that they share it in L2
-        const int order = p.block_table && p.max_kv_len >= 2 * p.max_q_len ? 1 : 0;
-        id = find_instance(0, p, 8, hpw, 32, 256, 0, order);              // LDS-ring kernel, two waves per SIMD (D = 128)
-        if (id < 0) id = find_instance(0, p, 4, hpw, 32, 256, 0, order);  // LDS-ring kernel, one wave per SIMD
+        // The rules below come from tuning a batch x length grid (profiles: configuration portability).
+        // Sequences of many query tiles, many sequences, or a cached prefix that dominates the key
+        // range: run the tiles of a sequence side by side so that they share its K/V in one L2.
+        const bool prefix = p.block_table && p.max_kv_len >= 2 * p.max_q_len;
+        const int order = (prefix || p.max_kv_len >= 2048 || p.num_seqs >= 32) ? 1 : 0;
+        // Short sequences: two small workgroups per compute unit hide each other's prologue and
+        // epilogue; long ones: one large workgroup with the deeper ring.
+        const bool small_wg = p.max_kv_len <= 2048;
+        id = find_instance(0, p, small_wg ? 4 : 8, hpw, 32, small_wg ? 128 : 256, 0, order);  // LDS-ring kernel (D = 128)
+        if (id < 0) id = find_instance(0, p, 8, hpw, 32, 256, 0, order);
+        if (id < 0) id = find_instance(0, p, 4, hpw, 32, 256, 0, order);
         if (id < 0) id = find_instance(0, p, 4, hpw, 64, 64 * 4, 0);  // register-staged kernel
     } else {
-        // With four or more KV heads a workgroup can own whole cache blocks (one wavefront per head):
-        // take the token-balanced kernel, one workgroup per compute unit.  Otherwise one KV head per
-        // workgroup and fixed parts: enough workgroups to fill the chip several times over, parts no
-        // shorter than 256 keys.
-        if (p.num_kv_heads >= 4) id = find_instance(1, p, 8, 16, 32, 0, -1);
+        // With four or more KV heads and enough keys to give every compute unit a long run, a workgroup
+        // owns whole cache blocks (one wavefront per head): the token-balanced kernel, one workgroup
+        // per compute unit.  Small batches of short contexts start and finish faster with one KV head
+        // per workgroup and fixed parts: enough workgroups to fill the chip several times over, parts
+        // no shorter than 256 keys.
+        const int64_t key_bound = (int64_t)p.num_seqs * p.max_kv_len;
+        if (p.num_kv_heads >= 4 && key_bound >= 100000) id = find_instance(1, p, 8, 16, 32, 0, -1);
         if (id < 0) {
             const int64_t units = (int64_t)p.num_seqs * p.num_kv_heads;
             int64_t want = units * (int64_t)p.max_kv_len / 2048;

@@ -107,9 +107,14 @@ def test_instance_tables_and_heuristic_selection():
     A.attn_clear_cache()
     A.attn_force_instance(False, -1)
     A.attn_force_instance(True, -1)
-    # GQA 32/8 prefill packs the 4 heads of a KV head into one workgroup
+    # GQA 32/8 prefill packs the 4 heads of a KV head into one workgroup; short sequences take the
+    # small workgroups (two per compute unit), long ones the large ring and the sequence-major grid
     i = A.attn_selected_instance(_args(), False)
-    assert "hpw4" in names_p[i] and "d128" in names_p[i]
+    assert "hpw4" in names_p[i] and "d128" in names_p[i] and "w4" in names_p[i] and "seqmajor" not in names_p[i]
+    i = A.attn_selected_instance(_args(max_kv_len=8192, max_q_len=8192), False)
+    assert "hpw4" in names_p[i] and "w8" in names_p[i] and "seqmajor" in names_p[i]
+    i = A.attn_selected_instance(_paged(max_kv_len=1536, max_q_len=512), False)  # a cached prefix twice the chunk
+    assert "seqmajor" in names_p[i]
     # MHA cannot
     i = A.attn_selected_instance(_args(num_kv_heads=32), False)
     assert "hpw1" in names_p[i]
@@ -123,6 +128,9 @@ def test_instance_tables_and_heuristic_selection():
     assert "balanced" in names_d[A.attn_selected_instance(long, True)]
     short = _paged(num_seqs=512, total_q=512, max_q_len=1, max_kv_len=200)
     assert "balanced" in names_d[A.attn_selected_instance(short, True)]
+    # a small batch of short contexts: one KV head per workgroup, fixed parts
+    small = _paged(num_seqs=4, total_q=4, max_q_len=1, max_kv_len=4096, block_table_stride=256)
+    assert names_d[A.attn_selected_instance(small, True)].startswith("decode_bf16 d128 w4 split")
     few_heads = _paged(num_seqs=512, total_q=512, max_q_len=1, max_kv_len=200, num_q_heads=4, num_kv_heads=1)
     assert "split0" in names_d[A.attn_selected_instance(few_heads, True)]
     # a forced instance that does not fit the shape is refused, not silently replaced
@@ -146,8 +154,10 @@ def test_cache_file_round_trip_stale_and_corrupt(tmp_path):
     good.write_text("attn-tune-cache-v1\n%s\t%s\t%s\t12.5\n" % (env_here, key, names_p[other]))
     assert A.attn_load_cache(str(good)) == 0
     assert A.attn_selected_instance(_args(), False) == other
-    # another bucket is untouched
-    assert A.attn_selected_instance(_args(max_kv_len=5000, max_q_len=5000), False) == default
+    # another bucket is untouched: it keeps the built-in choice for its own shape
+    far = _args(max_kv_len=5000, max_q_len=5000)
+    assert A.attn_selected_instance(far, False) != other
+    assert "seqmajor" in names_p[A.attn_selected_instance(far, False)] and "w8" in names_p[A.attn_selected_instance(far, False)]
     A.attn_clear_cache()
     assert A.attn_selected_instance(_args(), False) == default
     # stale environment (another device / build): entry ignored
