@@ -11,3 +11,4 @@ from .attn_oracle import (  # noqa: F401
     num_threads,
 )
 from .rmsnorm_oracle import rms_norm  # noqa: F401
+from .kv_write_oracle import kv_cache_write  # noqa: F401
