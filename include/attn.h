@@ -117,6 +117,34 @@ int attn_prefill_varlen(const attn_args *args, void *hip_stream);
 int attn_decode_paged(const attn_args *args, void *hip_stream);
 
 /*
+ * The step in front of paged attention: stores the keys and values of new tokens into the paged
+ * cache (the PagedAttention layout the paper cites; the paper itself is silent on this step).
+ * Token t goes to slot slot_mapping[t] = block * block_size + offset of both caches; a negative slot
+ * marks a padding token and stores nothing.  A pure copy (bit-exact), any element type of 2 or 4
+ * bytes.  Two tokens mapped to the same slot race.
+ */
+typedef struct attn_kv_write_args {
+    uint32_t struct_bytes; /* = sizeof(attn_kv_write_args) */
+    int32_t dtype;         /* attn_dtype: only the element size matters */
+    int32_t num_tokens;    /* T */
+    int32_t num_kv_heads;  /* Hkv */
+    int32_t head_dim;      /* D; D * element size is a multiple of 16 bytes */
+    int32_t block_size;    /* slots per cache block, > 0 */
+    int32_t num_blocks;    /* pool size, used only for validation */
+    int32_t reserved;
+    const void *k_new; /* [T, Hkv, D] */
+    const void *v_new;
+    int64_t new_stride_tok, new_stride_head; /* elements; rows 16-byte aligned */
+    void *k_cache; /* [num_blocks, block_size, Hkv, D] */
+    void *v_cache;
+    int64_t kv_stride_block, kv_stride_tok, kv_stride_head;
+    const int32_t *slot_mapping; /* int32 [T], device; slots >= num_blocks * block_size are undefined behaviour */
+} attn_kv_write_args;
+
+/* Enqueues the copy on `hip_stream`; allocates nothing, capturable.  ATTN_OK or a negative attn_status. */
+int attn_kv_cache_write(const attn_kv_write_args *args, void *hip_stream);
+
+/*
  * Bytes of workspace the call described by `args` may use (pure host function;
  * pointer fields are ignored).  is_decode = 1 for attn_decode_paged.
  * Returns 0 when args is NULL or malformed.

@@ -23,6 +23,9 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     make_args,
+    KvWriteArgs,
+    attn_kv_cache_write,
+    make_kv_write_args,
     RmsNormArgs,
     make_rmsnorm_args,
     rmsnorm_force_instance,

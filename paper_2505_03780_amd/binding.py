@@ -98,6 +98,8 @@ def load_library():
     lib.attn_force_instance.argtypes = [ctypes.c_int, ctypes.c_int]
     lib.attn_status_string.restype = ctypes.c_char_p
     lib.attn_status_string.argtypes = [ctypes.c_int]
+    lib.attn_kv_cache_write.restype = ctypes.c_int
+    lib.attn_kv_cache_write.argtypes = [ctypes.POINTER(KvWriteArgs), ctypes.c_void_p]
     R = ctypes.POINTER(RmsNormArgs)
     lib.rmsnorm_fused_add.restype = ctypes.c_int
     lib.rmsnorm_fused_add.argtypes = [R, ctypes.c_void_p]
@@ -113,6 +115,30 @@ def load_library():
     lib.rmsnorm_force_instance.argtypes = [ctypes.c_int]
     _lib = lib
     return lib
+
+
+class KvWriteArgs(ctypes.Structure):
+    """Mirror of ``attn_kv_write_args`` in include/attn.h."""
+    _fields_ = [
+        ("struct_bytes", ctypes.c_uint32),
+        ("dtype", ctypes.c_int32),
+        ("num_tokens", ctypes.c_int32),
+        ("num_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32),
+        ("block_size", ctypes.c_int32),
+        ("num_blocks", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
+        ("k_new", ctypes.c_void_p),
+        ("v_new", ctypes.c_void_p),
+        ("new_stride_tok", ctypes.c_int64),
+        ("new_stride_head", ctypes.c_int64),
+        ("k_cache", ctypes.c_void_p),
+        ("v_cache", ctypes.c_void_p),
+        ("kv_stride_block", ctypes.c_int64),
+        ("kv_stride_tok", ctypes.c_int64),
+        ("kv_stride_head", ctypes.c_int64),
+        ("slot_mapping", ctypes.c_void_p),
+    ]
 
 
 class RmsNormArgs(ctypes.Structure):
@@ -326,3 +352,37 @@ def rmsnorm_selected_instance(args: RmsNormArgs) -> int:
 
 def rmsnorm_force_instance(idx: int) -> None:
     load_library().rmsnorm_force_instance(int(idx))
+
+
+# ---- KV-cache write ----------------------------------------------------------------------------------
+
+def make_kv_write_args(k_new, v_new, k_cache, v_cache, slot_mapping) -> KvWriteArgs:
+    """k_new, v_new: [T, Hkv, D]; caches: [num_blocks, block_size, Hkv, D]; slot_mapping: int32 [T]."""
+    import torch
+
+    if slot_mapping.dtype != torch.int32 or not slot_mapping.is_contiguous():
+        raise TypeError("slot_mapping must be a contiguous int32 tensor")
+    for name, t in (("k_new", k_new), ("v_new", v_new), ("k_cache", k_cache), ("v_cache", v_cache)):
+        if t.stride(-1) != 1:
+            raise ValueError("%s: head_dim must be contiguous" % name)
+    if k_new.stride() != v_new.stride() or k_cache.stride() != v_cache.stride():
+        raise ValueError("K and V must share their strides")
+    a = KvWriteArgs()
+    a.struct_bytes = ctypes.sizeof(KvWriteArgs)
+    a.dtype = _dtype_code(k_new)
+    a.num_tokens, a.num_kv_heads, a.head_dim = int(k_new.shape[0]), int(k_new.shape[1]), int(k_new.shape[2])
+    a.block_size, a.num_blocks = int(k_cache.shape[1]), int(k_cache.shape[0])
+    a.k_new, a.v_new = _ptr(k_new), _ptr(v_new)
+    a.new_stride_tok, a.new_stride_head = k_new.stride(0), k_new.stride(1)
+    a.k_cache, a.v_cache = _ptr(k_cache), _ptr(v_cache)
+    a.kv_stride_block, a.kv_stride_tok, a.kv_stride_head = k_cache.stride(0), k_cache.stride(1), k_cache.stride(2)
+    a.slot_mapping = _ptr(slot_mapping)
+    return a
+
+
+def attn_kv_cache_write(k_new, v_new, k_cache, v_cache, slot_mapping, stream=None, args: Optional[KvWriteArgs] = None) -> None:
+    """Enqueue the scatter of new keys/values into the paged caches."""
+    a = args or make_kv_write_args(k_new, v_new, k_cache, v_cache, slot_mapping)
+    rc = load_library().attn_kv_cache_write(ctypes.byref(a), _stream_ptr(stream))
+    if rc != 0:
+        raise AttnError(rc, "attn_kv_cache_write")

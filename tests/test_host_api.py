@@ -225,3 +225,29 @@ def test_rmsnorm_validation_and_selection_on_the_host():
     A.rmsnorm_force_instance(-1)
     assert lib.rmsnorm_tune(None, None, 1, 0) == -1
     assert lib.rmsnorm_tune(_rms(hidden=12), None, 1, 0) == -4
+
+
+def test_kv_cache_write_validation_on_the_host():
+    lib = A.load_library()
+    a = A.KvWriteArgs()
+    a.struct_bytes = ctypes.sizeof(A.KvWriteArgs)
+    assert a.struct_bytes == 112
+    a.dtype, a.num_tokens, a.num_kv_heads, a.head_dim, a.block_size, a.num_blocks = A.ATTN_BF16, 4, 8, 128, 16, 10
+    a.k_new = a.v_new = 0x1000
+    a.k_cache = a.v_cache = 0x2000
+    a.slot_mapping = 0x3000
+    a.new_stride_tok, a.new_stride_head = 1024, 128
+    a.kv_stride_block, a.kv_stride_tok, a.kv_stride_head = 16 * 1024, 1024, 128
+    assert lib.attn_kv_cache_write(None, None) == -1
+    bad = A.KvWriteArgs.from_buffer_copy(a); bad.struct_bytes = 8
+    assert lib.attn_kv_cache_write(bad, None) == -2
+    bad = A.KvWriteArgs.from_buffer_copy(a); bad.dtype = 7
+    assert lib.attn_kv_cache_write(bad, None) == -3
+    bad = A.KvWriteArgs.from_buffer_copy(a); bad.head_dim = 100  # 200 bytes per head row
+    assert lib.attn_kv_cache_write(bad, None) == -4
+    bad = A.KvWriteArgs.from_buffer_copy(a); bad.slot_mapping = None
+    assert lib.attn_kv_cache_write(bad, None) == -1
+    bad = A.KvWriteArgs.from_buffer_copy(a); bad.kv_stride_tok = 100
+    assert lib.attn_kv_cache_write(bad, None) == -2
+    bad = A.KvWriteArgs.from_buffer_copy(a); bad.num_tokens = 0; bad.k_new = None
+    assert lib.attn_kv_cache_write(bad, None) == 0
