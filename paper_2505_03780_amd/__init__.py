@@ -5,6 +5,7 @@ library's HIP kernels.  PyTorch tensors only provide device memory and streams.
 """
 from .binding import (  # noqa: F401
     ATTN_BF16,
+    ATTN_F16,
     ATTN_F32,
     AttnArgs,
     AttnError,

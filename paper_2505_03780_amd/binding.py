@@ -10,7 +10,7 @@ import ctypes
 import os
 from typing import Optional
 
-ATTN_F32, ATTN_BF16 = 0, 1
+ATTN_F32, ATTN_BF16, ATTN_F16 = 0, 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libattn_gfx950.so")
@@ -170,7 +170,9 @@ def _dtype_code(t) -> int:
         return ATTN_BF16
     if t.dtype == torch.float32:
         return ATTN_F32
-    raise TypeError("q/k/v must be bfloat16 or float32 tensors")
+    if t.dtype == torch.float16:
+        return ATTN_F16
+    raise TypeError("tensors must be bfloat16, float16 or float32")
 
 
 def _ptr(t) -> Optional[int]:

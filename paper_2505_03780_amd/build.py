@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libattn_gfx950.so")
-SOURCES = ["attn_api.hip", "prefill_f32.hip", "prefill_bf16.hip", "prefill_bf16_ring.hip", "decode_bf16.hip", "rmsnorm.hip", "kv_write.hip"]
+SOURCES = ["attn_api.hip", "prefill_f32.hip", "prefill_bf16.hip", "prefill_bf16_ring.hip", "prefill_f16_ring.hip", "decode_bf16.hip", "decode_f16.hip", "rmsnorm.hip", "kv_write.hip"]
 # Packed fp32 instructions are switched off on purpose (see DESIGN notes in the repository root).
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -23,7 +23,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
 
 # The MFMA kernels never do arithmetic on NaN (garbage rows are replaced by selects before any use),
 # so the compiler may skip the canonicalising v_max it otherwise puts in front of every fmaxf.
-EXTRA = {"prefill_bf16_ring.hip": ["-fno-honor-nans"]}
+EXTRA = {"prefill_bf16_ring.hip": ["-fno-honor-nans"], "prefill_f16_ring.hip": ["-fno-honor-nans"]}
 
 
 def _compile(src: str) -> str:

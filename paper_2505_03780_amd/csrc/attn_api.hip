@@ -47,7 +47,9 @@ std::unordered_map<std::string, std::string> g_named;  // other kernel kinds: bu
 std::atomic<int> g_forced[2] = {{-1}, {-1}};
 bool g_env_cache_tried = false;
 
-const Instance *instances(int is_decode, int *n) { return is_decode ? decode_instances(n) : prefill_instances(n); }
+const Instance *all_decode_instances(int *count);
+const Instance *instances(int is_decode, int *n) { return is_decode ? all_decode_instances(n) : prefill_instances(n); }
+bool is16(int dtype) { return dtype == ATTN_BF16 || dtype == ATTN_F16; }
 
 int ilog2_ceil(int64_t x)
 {
@@ -62,8 +64,8 @@ int validate(const attn_args *a, int is_decode)
 {
     if (!a) return ATTN_ERR_NULL;
     if (a->struct_bytes != sizeof(attn_args)) return ATTN_ERR_SHAPE;
-    if (a->dtype != ATTN_F32 && a->dtype != ATTN_BF16) return ATTN_ERR_DTYPE;
-    if (is_decode && a->dtype != ATTN_BF16) return ATTN_ERR_DTYPE;
+    if (a->dtype != ATTN_F32 && !is16(a->dtype)) return ATTN_ERR_DTYPE;
+    if (is_decode && !is16(a->dtype)) return ATTN_ERR_DTYPE;
     if (a->num_seqs < 0 || a->num_q_heads <= 0 || a->num_kv_heads <= 0 || a->total_q < 0 || a->max_q_len < 0 ||
         a->max_kv_len < 0)
         return ATTN_ERR_SHAPE;
@@ -71,7 +73,7 @@ int validate(const attn_args *a, int is_decode)
     if (a->head_dim != 64 && a->head_dim != 128) return ATTN_ERR_UNSUPPORTED;
     if (is_decode && a->total_q != a->num_seqs) return ATTN_ERR_SHAPE;
     if (is_decode && a->max_q_len > 1) return ATTN_ERR_SHAPE;
-    const int vec = a->dtype == ATTN_BF16 ? 8 : 1;  // elements per 16-byte vector access
+    const int vec = is16(a->dtype) ? 8 : 1;  // elements per 16-byte vector access
     if (a->q_stride_head < a->head_dim || a->o_stride_head < a->head_dim || a->kv_stride_head < a->head_dim ||
         a->q_stride_tok <= 0 || a->o_stride_tok <= 0 || a->kv_stride_tok <= 0)
         return ATTN_ERR_SHAPE;
@@ -90,7 +92,7 @@ int validate(const attn_args *a, int is_decode)
     if (!a->q || !a->out || !a->seq_lens) return ATTN_ERR_NULL;
     if (a->max_kv_len > 0 && (!a->k || !a->v)) return ATTN_ERR_NULL;
     if (!is_decode && !a->query_start_loc) return ATTN_ERR_NULL;
-    if (a->dtype == ATTN_BF16) {
+    if (is16(a->dtype)) {
         const uintptr_t bits = (uintptr_t)a->q | (uintptr_t)a->out | (uintptr_t)a->k | (uintptr_t)a->v;
         if (bits & 15) return ATTN_ERR_SHAPE;  // 128-bit accesses
     }
@@ -100,6 +102,7 @@ int validate(const attn_args *a, int is_decode)
 KParams to_kparams(const attn_args *a, int is_decode)
 {
     KParams p{};
+    p.dtype = a->dtype;
     p.q = a->q;
     p.out = a->out;
     p.k = a->k;
@@ -141,7 +144,7 @@ std::string bucket_key(const KParams &p, int dtype, int is_decode)
 {
     char buf[192];
     snprintf(buf, sizeof buf, "%s|%s|d%d|hq%d|hkv%d|%s|bs%d|c%d|B%d|q%d|kv%d", is_decode ? "decode" : "prefill",
-             dtype == ATTN_BF16 ? "bf16" : "f32", p.head_dim, p.num_q_heads, p.num_kv_heads,
+             dtype == ATTN_BF16 ? "bf16" : dtype == ATTN_F16 ? "f16" : "f32", p.head_dim, p.num_q_heads, p.num_kv_heads,
              p.block_table ? "paged" : "contig", p.block_size, p.causal, ilog2_ceil(std::max(1, p.num_seqs)),
              ilog2_ceil(std::max(1, p.max_q_len)), ilog2_ceil(std::max(1, p.max_kv_len)));
     return buf;
@@ -251,6 +254,8 @@ int heuristic(const KParams &p, int is_decode)
             if (sl >= p.max_kv_len) sl = 0;
             id = find_instance(1, p, 4, 16, 32, 0, sl);
             if (id < 0) id = find_instance(1, p, 4, 16, 32, 0, 0);
+            if (id < 0) id = find_instance(1, p, 8, 16, 32, 0, sl);  // fp16 has the wave-per-head family only
+            if (id < 0) id = find_instance(1, p, 8, 16, 32, 0, 0);
         }
     }
     if (id >= 0) return id;
@@ -423,11 +428,25 @@ int run(const attn_args *a, int is_decode, hipStream_t stream, int instance_over
     }
     if (t[id].launch(p, stream) != hipSuccess) return ATTN_ERR_HIP;
     // fixed-split decode merges its parts with a second kernel (the token-balanced launcher brings its own)
-    if (is_decode && t[id].split_len >= 0 && p.num_splits > 1 && launch_decode_combine(p, stream) != hipSuccess) return ATTN_ERR_HIP;
+    if (is_decode && t[id].split_len >= 0 && p.num_splits > 1 &&
+        (p.dtype == kDtypeF16 ? launch_decode_combine_f16(p, stream) : launch_decode_combine(p, stream)) != hipSuccess)
+        return ATTN_ERR_HIP;
     return ATTN_OK;
 }
 
 // ---- tuner ----------------------------------------------------------------------------------------
+
+// same values as fill_bf16_kernel, stored as fp16
+__global__ void fill_f16_kernel(_Float16 *dst, size_t n, uint32_t seed)
+{
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+        uint32_t h = (uint32_t)i * 2654435761u ^ seed;
+        h ^= h >> 15;
+        h *= 2246822519u;
+        h ^= h >> 13;
+        dst[i] = (_Float16)(((int)(h & 0xffff) - 32768) * (1.f / 16384.f));
+    }
+}
 
 __global__ void fill_bf16_kernel(uint16_t *dst, size_t n, uint32_t seed)
 {
@@ -455,7 +474,7 @@ int tune(const attn_args *shape, int is_decode, const char *cache_path, int iter
 {
     if (!shape) return ATTN_ERR_NULL;
     if (shape->struct_bytes != sizeof(attn_args)) return ATTN_ERR_SHAPE;
-    if (shape->dtype != ATTN_BF16) return ATTN_ERR_DTYPE;  // the fp32 path has a single kernel
+    if (!is16(shape->dtype)) return ATTN_ERR_DTYPE;  // the fp32 path has a single kernel
     if (shape->num_seqs <= 0 || shape->num_q_heads <= 0 || shape->num_kv_heads <= 0 ||
         shape->num_q_heads % shape->num_kv_heads || shape->max_kv_len <= 0)
         return ATTN_ERR_SHAPE;
@@ -526,9 +545,15 @@ int tune(const attn_args *shape, int is_decode, const char *cache_path, int iter
         (void)hipGetLastError();
         return ATTN_ERR_HIP;
     }
-    hipLaunchKernelGGL(fill_bf16_kernel, dim3(1024), dim3(256), 0, 0, (uint16_t *)dq.p, q_elems, 1u);
-    hipLaunchKernelGGL(fill_bf16_kernel, dim3(4096), dim3(256), 0, 0, (uint16_t *)dk.p, kv_elems, 2u);
-    hipLaunchKernelGGL(fill_bf16_kernel, dim3(4096), dim3(256), 0, 0, (uint16_t *)dv.p, kv_elems, 3u);
+    if (shape->dtype == ATTN_F16) {
+        hipLaunchKernelGGL(fill_f16_kernel, dim3(1024), dim3(256), 0, 0, (_Float16 *)dq.p, q_elems, 1u);
+        hipLaunchKernelGGL(fill_f16_kernel, dim3(4096), dim3(256), 0, 0, (_Float16 *)dk.p, kv_elems, 2u);
+        hipLaunchKernelGGL(fill_f16_kernel, dim3(4096), dim3(256), 0, 0, (_Float16 *)dv.p, kv_elems, 3u);
+    } else {
+        hipLaunchKernelGGL(fill_bf16_kernel, dim3(1024), dim3(256), 0, 0, (uint16_t *)dq.p, q_elems, 1u);
+        hipLaunchKernelGGL(fill_bf16_kernel, dim3(4096), dim3(256), 0, 0, (uint16_t *)dk.p, kv_elems, 2u);
+        hipLaunchKernelGGL(fill_bf16_kernel, dim3(4096), dim3(256), 0, 0, (uint16_t *)dv.p, kv_elems, 3u);
+    }
     bool ok = hipMemcpy(dqsl.p, qsl.data(), (B + 1) * 4, hipMemcpyHostToDevice) == hipSuccess &&
               hipMemcpy(dkvsl.p, kvsl.data(), (B + 1) * 4, hipMemcpyHostToDevice) == hipSuccess &&
               hipMemcpy(dlens.p, lens.data(), B * 4, hipMemcpyHostToDevice) == hipSuccess;
@@ -709,6 +734,23 @@ bool lookup_named_winner(const std::string &key, std::string *instance_name)
 
 void load_env_cache_once() { maybe_load_env_cache(); }
 
+namespace {
+const Instance *all_decode_instances(int *count)
+{
+    static const std::vector<Instance> all = [] {
+        std::vector<Instance> v;
+        int n;
+        const Instance *t = decode_instances(&n);
+        v.insert(v.end(), t, t + n);
+        t = decode_f16_instances(&n);
+        v.insert(v.end(), t, t + n);
+        return v;
+    }();
+    *count = (int)all.size();
+    return all.data();
+}
+}  // namespace
+
 const Instance *prefill_instances(int *count)
 {
     static const std::vector<Instance> all = [] {
@@ -717,6 +759,8 @@ const Instance *prefill_instances(int *count)
         const Instance *t = prefill_ring_instances(&n);
         v.insert(v.end(), t, t + n);
         t = prefill_staged_instances(&n);
+        v.insert(v.end(), t, t + n);
+        t = prefill_ring_f16_instances(&n);
         v.insert(v.end(), t, t + n);
         return v;
     }();
@@ -789,7 +833,7 @@ int attn_selected_instance(const attn_args *a, int is_decode)
 {
     is_decode = is_decode ? 1 : 0;
     if (!a || a->struct_bytes != sizeof(attn_args)) return ATTN_ERR_NULL;
-    if (a->dtype != ATTN_BF16) return ATTN_ERR_DTYPE;
+    if (!is16(a->dtype)) return ATTN_ERR_DTYPE;
     if (a->num_q_heads <= 0 || a->num_kv_heads <= 0 || a->num_q_heads % a->num_kv_heads) return ATTN_ERR_SHAPE;
     const KParams p = to_kparams(a, is_decode);
     return select_instance(p, a->dtype, is_decode);

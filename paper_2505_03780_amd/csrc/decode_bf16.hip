@@ -23,7 +23,21 @@
 namespace attn {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+// This file is compiled twice: as it stands for bf16, and included by decode_f16.hip with
+// ATTN_DECODE_ELEM_F16 defined for fp16 caches (the element type only changes the MFMA opcode and the
+// conversions of weights and outputs; a smaller set of instances is built).
+#ifdef ATTN_DECODE_ELEM_F16
+typedef _Float16 elem_t;
+#define DECODE_MFMA __builtin_amdgcn_mfma_f32_16x16x32_f16
+#define DECODE_NAME "decode_f16"
+constexpr int kElemDtype = kDtypeF16;
+#else
+typedef __bf16 elem_t;
+#define DECODE_MFMA __builtin_amdgcn_mfma_f32_16x16x32_bf16
+#define DECODE_NAME "decode_bf16"
+constexpr int kElemDtype = kDtypeBf16;
+#endif
+typedef elem_t ex8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
@@ -73,23 +87,23 @@ __global__ __launch_bounds__(WAVES * 64) void decode_bf16_kernel(const KParams p
     const int G = p.group;
 
     // ---- Q fragment (B operand): lane holds head column l16, channels 32*ks + 8*lg .. +7 ----
-    bf16x8 qf[KS];
+    ex8 qf[KS];
     {
-        const __bf16 *qrow = (const __bf16 *)p.q + (int64_t)s * p.q_stride_tok +
+        const elem_t *qrow = (const elem_t *)p.q + (int64_t)s * p.q_stride_tok +
                              (int64_t)(kvh * G + (l16 < G ? l16 : 0)) * p.q_stride_head + 8 * lg;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            bf16x8 t = *(const bf16x8 *)(qrow + 32 * ks);
+            ex8 t = *(const ex8 *)(qrow + 32 * ks);
             if (l16 >= G) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) t[e] = (__bf16)0.f;
+                for (int e = 0; e < 8; ++e) t[e] = (elem_t)0.f;
             }
             qf[ks] = t;
         }
     }
 
-    const __bf16 *kbase = (const __bf16 *)p.k + (int64_t)kvh * p.kv_stride_head;
-    const __bf16 *vbase = (const __bf16 *)p.v + (int64_t)kvh * p.kv_stride_head;
+    const elem_t *kbase = (const elem_t *)p.k + (int64_t)kvh * p.kv_stride_head;
+    const elem_t *vbase = (const elem_t *)p.v + (int64_t)kvh * p.kv_stride_head;
     const int32_t *bt_row = p.block_table + (int64_t)s * p.block_table_stride;
     unsigned char *vst = lds + wave * C::kVBytes;
 
@@ -105,14 +119,14 @@ __global__ __launch_bounds__(WAVES * 64) void decode_bf16_kernel(const KParams p
         const int64_t g0 = group_offset(c0), g1 = group_offset(c0 + 16);
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            const __bf16 *kr = kbase + (t ? g1 : g0) + (int64_t)l16 * p.kv_stride_tok + 8 * lg;
+            const elem_t *kr = kbase + (t ? g1 : g0) + (int64_t)l16 * p.kv_stride_tok + 8 * lg;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) kreg[t][ks] = *(const u32x4 *)(kr + 32 * ks);
         }
 #pragma unroll
         for (int i = 0; i < VLD; ++i) {
             const int row = lane / (HD / 8) + VROWS * i;  // 0..31
-            const __bf16 *vr = vbase + (row < 16 ? g0 : g1) + (int64_t)(row & 15) * p.kv_stride_tok + 8 * (lane % (HD / 8));
+            const elem_t *vr = vbase + (row < 16 ? g0 : g1) + (int64_t)(row & 15) * p.kv_stride_tok + 8 * (lane % (HD / 8));
             vreg[i] = *(const u32x4 *)vr;
         }
     };
@@ -135,7 +149,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_bf16_kernel(const KParams p
             sacc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
-                sacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kreg[t][ks]), qf[ks], sacc[t], 0, 0, 0);
+                sacc[t] = DECODE_MFMA(__builtin_bit_cast(ex8, kreg[t][ks]), qf[ks], sacc[t], 0, 0, 0);
         }
         const bool tail = c0 + kChunk > k_hi;
 #pragma unroll
@@ -165,13 +179,13 @@ __global__ __launch_bounds__(WAVES * 64) void decode_bf16_kernel(const KParams p
         const float m_new = fmaxf(m_run, mloc);  // finite: key c0 < k_hi is unmasked
         const float alpha = fast_exp2(m_run - m_new);
         m_run = m_new;
-        bf16x8 pf;
+        ex8 pf;
         float rowsum = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const float w = fast_exp2(x[e] - m_new);
             rowsum += w;
-            pf[e] = (__bf16)w;
+            pf[e] = (elem_t)w;
         }
         l_run = l_run * alpha + rowsum;
 #pragma unroll
@@ -184,7 +198,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_bf16_kernel(const KParams p
             const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)a);
             const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a + 16 * C::kVPitch));
             const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            oacc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, both), pf, oacc[db], 0, 0, 0);
+            oacc[db] = DECODE_MFMA(__builtin_bit_cast(ex8, both), pf, oacc[db], 0, 0, 0);
         }
     }
 
@@ -222,8 +236,8 @@ __global__ __launch_bounds__(WAVES * 64) void decode_bf16_kernel(const KParams p
         }
         const int head = kvh * G + hq;
         if (p.num_splits == 1) {
-            __bf16 *o = (__bf16 *)p.out + (int64_t)s * p.o_stride_tok + (int64_t)head * p.o_stride_head;
-            o[d] = (__bf16)(L > 0.f ? O / L : 0.f);
+            elem_t *o = (elem_t *)p.out + (int64_t)s * p.o_stride_tok + (int64_t)head * p.o_stride_head;
+            o[d] = (elem_t)(L > 0.f ? O / L : 0.f);
         } else {
             float *w = p.workspace + (((int64_t)s * p.num_q_heads + head) * p.num_splits + part) * (HD + 2);
             w[d] = O;
@@ -256,7 +270,7 @@ __device__ __forceinline__ void decode_stream_part(const KParams &p, unsigned ch
         if (l16 < G) {
             const int head = kvh * G + l16;
             if (partial_base == nullptr) {
-                __bf16 *o = (__bf16 *)p.out + (int64_t)s * p.o_stride_tok + (int64_t)head * p.o_stride_head;
+                elem_t *o = (elem_t *)p.out + (int64_t)s * p.o_stride_tok + (int64_t)head * p.o_stride_head;
                 for (int d = 4 * lg; d < HD; d += 16) *(uint2 *)(o + d) = uint2{0u, 0u};
             } else {
                 float *w = partial_base + (int64_t)head * head_stride;
@@ -270,16 +284,16 @@ __device__ __forceinline__ void decode_stream_part(const KParams &p, unsigned ch
         return;
     }
 
-    bf16x8 qf[KS];
+    ex8 qf[KS];
     {
-        const __bf16 *qrow = (const __bf16 *)p.q + (int64_t)s * p.q_stride_tok +
+        const elem_t *qrow = (const elem_t *)p.q + (int64_t)s * p.q_stride_tok +
                              (int64_t)(kvh * G + (l16 < G ? l16 : 0)) * p.q_stride_head + 8 * lg;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            bf16x8 t = *(const bf16x8 *)(qrow + 32 * ks);
+            ex8 t = *(const ex8 *)(qrow + 32 * ks);
             if (l16 >= G) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) t[e] = (__bf16)0.f;
+                for (int e = 0; e < 8; ++e) t[e] = (elem_t)0.f;
             }
             qf[ks] = t;
         }
@@ -340,7 +354,7 @@ __device__ __forceinline__ void decode_stream_part(const KParams &p, unsigned ch
             sacc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
-                sacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.k[t][ks]), qf[ks], sacc[t], 0, 0, 0);
+                sacc[t] = DECODE_MFMA(__builtin_bit_cast(ex8, r.k[t][ks]), qf[ks], sacc[t], 0, 0, 0);
         }
         const bool tail = c0 + kChunk > k_hi;
 #pragma unroll
@@ -369,13 +383,13 @@ __device__ __forceinline__ void decode_stream_part(const KParams &p, unsigned ch
         const float m_new = fmaxf(m_run, mloc);  // finite: key c0 < k_hi is unmasked
         const float alpha = fast_exp2(m_run - m_new);
         m_run = m_new;
-        bf16x8 pf;
+        ex8 pf;
         float rowsum = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const float w = fast_exp2(x[e] - m_new);
             rowsum += w;
-            pf[e] = (__bf16)w;
+            pf[e] = (elem_t)w;
         }
         l_run = l_run * alpha + rowsum;
 #pragma unroll
@@ -386,7 +400,7 @@ __device__ __forceinline__ void decode_stream_part(const KParams &p, unsigned ch
             const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)a);
             const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a + 16 * C::kVPitch));
             const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            oacc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, both), pf, oacc[db], 0, 0, 0);
+            oacc[db] = DECODE_MFMA(__builtin_bit_cast(ex8, both), pf, oacc[db], 0, 0, 0);
         }
     };
 
@@ -424,15 +438,15 @@ __device__ __forceinline__ void decode_stream_part(const KParams &p, unsigned ch
     if (l16 < G) {
         const int head = kvh * G + l16;
         if (partial_base == nullptr) {
-            __bf16 *o = (__bf16 *)p.out + (int64_t)s * p.o_stride_tok + (int64_t)head * p.o_stride_head;
+            elem_t *o = (elem_t *)p.out + (int64_t)s * p.o_stride_tok + (int64_t)head * p.o_stride_head;
             const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
-                typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-                bf16x4 w;
+                typedef elem_t ex4 __attribute__((ext_vector_type(4)));
+                ex4 w;
 #pragma unroll
-                for (int v = 0; v < 4; ++v) w[v] = (__bf16)(oacc[db][v] * inv);
-                *(bf16x4 *)(o + db * 16 + 4 * lg) = w;
+                for (int v = 0; v < 4; ++v) w[v] = (elem_t)(oacc[db][v] * inv);
+                *(ex4 *)(o + db * 16 + 4 * lg) = w;
             }
         } else {
             float *w = partial_base + (int64_t)head * head_stride;
@@ -489,7 +503,7 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void decode_seq_kernel(const
 // memory round trip per block instead of several per part.  A part that was never written must not
 // be passed; m = -inf (a part without keys) gets weight zero.
 template <int HD>
-__device__ __forceinline__ void merge_head(const float *r, int parts, int64_t stride, int lane, __bf16 *o)
+__device__ __forceinline__ void merge_head(const float *r, int parts, int64_t stride, int lane, elem_t *o)
 {
     constexpr int CPL = HD / 32;  // 4 or 2 channels per lane
     const int sub = lane & 31;
@@ -538,11 +552,11 @@ __device__ __forceinline__ void merge_head(const float *r, int parts, int64_t st
         }
     }
     const float inv = L > 0.f ? 1.f / L : 0.f;
-    typedef __bf16 bf16xC __attribute__((ext_vector_type(CPL)));
-    bf16xC w;
+    typedef elem_t exC __attribute__((ext_vector_type(CPL)));
+    exC w;
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) w[c] = (__bf16)(acc[c] * inv);
-    *(bf16xC *)o = w;
+    for (int c = 0; c < CPL; ++c) w[c] = (elem_t)(acc[c] * inv);
+    *(exC *)o = w;
 }
 
 // One wavefront merges query heads 2*pair and 2*pair + 1 of the G heads of (sequence s, KV head kvh).
@@ -554,7 +568,7 @@ __device__ __forceinline__ void merge_pair(const KParams &p, int lane, int s, in
     const int G = p.group;
     const int hl = 2 * pair + (lane >> 5);
     const int hc = hl < G ? hl : G - 1;  // an idle half repeats the last head (same values, same address)
-    __bf16 *o = (__bf16 *)p.out + (int64_t)s * p.o_stride_tok + (int64_t)(kvh * G + hc) * p.o_stride_head + (HD / 32) * (lane & 31);
+    elem_t *o = (elem_t *)p.out + (int64_t)s * p.o_stride_tok + (int64_t)(kvh * G + hc) * p.o_stride_head + (HD / 32) * (lane & 31);
     merge_head<HD>(rec + (int64_t)hc * head_stride, parts, part_stride, lane, o);
 }
 
@@ -695,7 +709,7 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(const KParams p)
 template <int HD, int WAVES>
 bool decode_valid(const KParams &p)
 {
-    return p.head_dim == HD && p.group <= 16 && p.block_table != nullptr && p.block_size >= 16;
+    return p.dtype == kElemDtype && p.head_dim == HD && p.group <= 16 && p.block_table != nullptr && p.block_size >= 16;
 }
 
 template <int HD, int WAVES>
@@ -739,24 +753,53 @@ hipError_t decode_balanced_launch(const KParams &p, hipStream_t stream)
 // SPLIT < 0 marks the token-balanced variant with -SPLIT workgroups per compute unit
 #define DECODE_BAL_INSTANCE(HD, WAVES, PER_CU)                                                                  \
     {                                                                                                          \
-        "decode_bf16_balanced d" #HD " w" #WAVES " percu" #PER_CU, 16, kChunk, WAVES, 16, 2, -PER_CU,            \
+        DECODE_NAME "_balanced d" #HD " w" #WAVES " percu" #PER_CU, 16, kChunk, WAVES, 16, 2, -PER_CU,            \
             decode_valid<HD, WAVES>, decode_balanced_launch<HD, WAVES>                                         \
     }
 
 #define DECODE_SEQ_INSTANCE(HD, WAVES, SPLIT)                                                                  \
     {                                                                                                          \
-        "decode_bf16_seq d" #HD " w" #WAVES " split" #SPLIT, 16, kChunk, WAVES, 16, 2, SPLIT, decode_valid<HD, WAVES>, \
+        DECODE_NAME "_seq d" #HD " w" #WAVES " split" #SPLIT, 16, kChunk, WAVES, 16, 2, SPLIT, decode_valid<HD, WAVES>, \
             decode_seq_launch<HD, WAVES>                                                                       \
     }
 
 #define DECODE_INSTANCE(HD, WAVES, SPLIT)                                                                     \
     {                                                                                                         \
-        "decode_bf16 d" #HD " w" #WAVES " split" #SPLIT, 16, kChunk, WAVES, 16, 2, SPLIT, decode_valid<HD, WAVES>, \
+        DECODE_NAME " d" #HD " w" #WAVES " split" #SPLIT, 16, kChunk, WAVES, 16, 2, SPLIT, decode_valid<HD, WAVES>, \
             decode_launch<HD, WAVES>                                                                          \
     }
 
 }  // namespace
 
+#ifdef ATTN_DECODE_ELEM_F16
+hipError_t launch_decode_combine_f16(const KParams &p, hipStream_t stream)
+{
+    const int64_t blocks = (int64_t)p.num_seqs * p.num_kv_heads * ((p.group + 1) / 2);
+    if (blocks <= 0) return hipSuccess;
+    if (blocks > 0x7fffffff) return hipErrorInvalidConfiguration;
+    if (p.head_dim == 128)
+        hipLaunchKernelGGL(decode_combine_kernel<128>, dim3((unsigned)blocks), dim3(64), 0, stream, p);
+    else if (p.head_dim == 64)
+        hipLaunchKernelGGL(decode_combine_kernel<64>, dim3((unsigned)blocks), dim3(64), 0, stream, p);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+const Instance *decode_f16_instances(int *count)
+{
+    static const Instance table[] = {
+        DECODE_SEQ_INSTANCE(128, 8, 0),    DECODE_SEQ_INSTANCE(128, 8, 256),  DECODE_SEQ_INSTANCE(128, 8, 512),
+        DECODE_SEQ_INSTANCE(128, 8, 1024), DECODE_SEQ_INSTANCE(128, 8, 2048), DECODE_SEQ_INSTANCE(128, 4, 256),
+        DECODE_SEQ_INSTANCE(128, 4, 512),  DECODE_SEQ_INSTANCE(128, 4, 1024), DECODE_SEQ_INSTANCE(64, 8, 256),
+        DECODE_SEQ_INSTANCE(64, 4, 512),   DECODE_BAL_INSTANCE(128, 8, 1),    DECODE_BAL_INSTANCE(128, 4, 1),
+        DECODE_BAL_INSTANCE(128, 8, 2),    DECODE_BAL_INSTANCE(64, 8, 1),
+    };
+    *count = (int)(sizeof(table) / sizeof(table[0]));
+    return table;
+}
+
+#else
 hipError_t launch_decode_combine(const KParams &p, hipStream_t stream)
 {
     const int64_t blocks = (int64_t)p.num_seqs * p.num_kv_heads * ((p.group + 1) / 2);
@@ -790,5 +833,7 @@ const Instance *decode_instances(int *count)
     *count = (int)(sizeof(table) / sizeof(table[0]));
     return table;
 }
+
+#endif
 
 }  // namespace attn

@@ -11,6 +11,9 @@
 
 namespace attn {
 
+// element types of q, k, v, out (the values of attn_dtype in the C ABI)
+constexpr int kDtypeF32 = 0, kDtypeBf16 = 1, kDtypeF16 = 2;
+
 struct KParams {
     const void *q;
     void *out;
@@ -23,6 +26,7 @@ struct KParams {
     int64_t q_stride_tok, q_stride_head;
     int64_t o_stride_tok, o_stride_head;
     int64_t kv_stride_block, kv_stride_tok, kv_stride_head;
+    int32_t dtype;  // kDtype*
     int32_t num_seqs, num_q_heads, num_kv_heads, head_dim;
     int32_t group;  // Hq / Hkv
     int32_t block_table_stride;
@@ -58,12 +62,15 @@ struct Instance {
 };
 
 const Instance *prefill_instances(int *count);         // all prefill instances, ring variants first
-const Instance *prefill_ring_instances(int *count);    // LDS-ring, software-pipelined (D = 128)
+const Instance *prefill_ring_instances(int *count);    // LDS-ring, software-pipelined (D = 128), bf16
+const Instance *prefill_ring_f16_instances(int *count);  // the same kernel for fp16
 const Instance *prefill_staged_instances(int *count);  // register-staged double buffer (D = 64, 128)
-const Instance *decode_instances(int *count);
+const Instance *decode_instances(int *count);       // bf16
+const Instance *decode_f16_instances(int *count);   // fp16: the wave-per-head and token-balanced kernels
 
 hipError_t launch_prefill_f32(const KParams &, hipStream_t);
 hipError_t launch_decode_combine(const KParams &, hipStream_t);
+hipError_t launch_decode_combine_f16(const KParams &, hipStream_t);
 
 // Floats per (sequence, query head, split) in the split-K workspace: D partial
 // outputs followed by the running max and the running sum.

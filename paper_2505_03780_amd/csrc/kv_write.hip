@@ -48,7 +48,7 @@ extern "C" int attn_kv_cache_write(const attn_kv_write_args *a, void *hip_stream
     using namespace attn;
     if (!a) return ATTN_ERR_NULL;
     if (a->struct_bytes != sizeof(attn_kv_write_args)) return ATTN_ERR_SHAPE;
-    if (a->dtype != ATTN_BF16 && a->dtype != ATTN_F32) return ATTN_ERR_DTYPE;
+    if (a->dtype != ATTN_BF16 && a->dtype != ATTN_F32 && a->dtype != ATTN_F16) return ATTN_ERR_DTYPE;
     const int esz = a->dtype == ATTN_F32 ? 4 : 2;
     if (a->num_tokens < 0 || a->num_kv_heads <= 0 || a->head_dim <= 0 || a->block_size <= 0 || a->num_blocks <= 0) return ATTN_ERR_SHAPE;
     if ((a->head_dim * esz) % 16 != 0) return ATTN_ERR_UNSUPPORTED;

@@ -294,7 +294,7 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_bf16_kernel(const KParams 
 template <int HD, int BN, int QB, int WAVES, int HPW>
 bool prefill_valid(const KParams &p)
 {
-    return p.head_dim == HD && p.group % HPW == 0;
+    return p.dtype == kDtypeBf16 && p.head_dim == HD && p.group % HPW == 0;
 }
 
 template <int HD, int BN, int QB, int WAVES, int HPW>

@@ -1,4 +1,4 @@
-// Causal variable-length prefill on bf16 MFMA (gfx950): LDS-ring, software-pipelined variant.
+// Causal variable-length prefill on bf16 (or fp16) MFMA (gfx950): LDS-ring, software-pipelined variant.
 //
 // Same operation and same operand layout as prefill_bf16.hip (tiled online-softmax
 // attention, the FlashAttention-2 formulation of the paper's kernel, section
@@ -26,7 +26,29 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// The two 16-bit element types the kernel is instantiated for: how a 32x32x16 product, the packing of
+// two weights and the sum of a packed pair are spelled.  Everything else (transfers, swizzles,
+// transposing reads, masks, the fp32 softmax) is the same code.
+struct ElemBf16 {
+    typedef __bf16 elem;
+    typedef bf16x8 x8;
+    typedef bf16x2 x2;
+    static constexpr int kDtype = kDtypeBf16;
+    static __device__ __forceinline__ f32x16 mfma(x8 a, x8 b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
+    static __device__ __forceinline__ float dot2(x2 a, x2 b, float c) { return __builtin_amdgcn_fdot2_f32_bf16(a, b, c, false); }
+};
+struct ElemF16 {
+    typedef _Float16 elem;
+    typedef f16x8 x8;
+    typedef f16x2 x2;
+    static constexpr int kDtype = kDtypeF16;
+    static __device__ __forceinline__ f32x16 mfma(x8 a, x8 b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
+    static __device__ __forceinline__ float dot2(x2 a, x2 b, float c) { return __builtin_amdgcn_fdot2(a, b, c, false); }
+};
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -103,10 +125,13 @@ struct RingCfg {
     static_assert(kLdsBytes >= (size_t)kWaves * kWaveTok * kHD * 2, "epilogue staging must fit in the ring");
 };
 
-template <int QB, int HPW, int NSLOT, int PF, int WAVES, bool PAGED>
+template <typename E, int QB, int HPW, int NSLOT, int PF, int WAVES, bool PAGED>
 __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void prefill_ring_kernel(const KParams p)
 {
     using C = RingCfg<QB, HPW, NSLOT, PF, WAVES>;
+    using elem = typename E::elem;
+    using x8 = typename E::x8;
+    using x2 = typename E::x2;
     constexpr int KSTEPS = kHD / 16;
     constexpr int DB = kHD / 32;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -153,18 +178,18 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
     const bool negate_q = p.scale_log2e < 0.f;
 
     // ---- Q fragments ---------------------------------------------------------------------------
-    const __bf16 *qbase = (const __bf16 *)p.q;
-    bf16x8 qf[QB][KSTEPS];
+    const elem *qbase = (const elem *)p.q;
+    x8 qf[QB][KSTEPS];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         int t = t0w + qb * 32 + l32;
         t = t < n_q ? t : n_q - 1;
-        const __bf16 *src = qbase + (int64_t)(q0 + t) * p.q_stride_tok + (int64_t)head * p.q_stride_head + 8 * lhalf;
+        const elem *src = qbase + (int64_t)(q0 + t) * p.q_stride_tok + (int64_t)head * p.q_stride_head + 8 * lhalf;
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
             u32x4 raw = *(const u32x4 *)(src + 16 * ks);
             if (negate_q) raw ^= 0x80008000u;
-            qf[qb][ks] = __builtin_bit_cast(bf16x8, raw);
+            qf[qb][ks] = __builtin_bit_cast(x8, raw);
         }
     }
 
@@ -176,7 +201,7 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
     }
     const int n_units = (kv_end + kUnit - 1) / kUnit;
 
-    __bf16 *obase = (__bf16 *)p.out;
+    elem *obase = (elem *)p.out;
     if (n_units == 0) {  // no visible key at all (non-causal call on an empty context): zeros
         for (int i = lane; i < C::kWaveTok * (kHD / 8); i += 64) {
             const int t = t0w + i / (kHD / 8);
@@ -315,9 +340,9 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
     // S(u) = K(u) Q^T for both query blocks
     auto qk = [&](int unit, f32x16 (&sacc)[QB]) {
         const unsigned char *kt = lds + (unit % NSLOT) * kSlotBytes;
-        bf16x8 kf[KSTEPS];
+        x8 kf[KSTEPS];
 #pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) kf[ks] = *(const bf16x8 *)(kt + koff[ks]);
+        for (int ks = 0; ks < KSTEPS; ++ks) kf[ks] = *(const x8 *)(kt + koff[ks]);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
@@ -325,7 +350,7 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb) sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[qb][ks], sacc[qb], 0, 0, 0);
+            for (int qb = 0; qb < QB; ++qb) sacc[qb] = E::mfma(kf[ks], qf[qb][ks], sacc[qb]);
         }
     };
     // Move the reference of the rows whose new maximum outgrew it by more than the slack; rare, and
@@ -374,11 +399,11 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
         move_reference(bm);
     };
     // P = 2^(x - ref) as bf16 B operands; row sums are taken over the rounded values
-    auto exponentiate = [&](const f32x16 (&sacc)[QB], bf16x8 (&pf)[QB][2], auto mask_tag) {
+    auto exponentiate = [&](const f32x16 (&sacc)[QB], x8 (&pf)[QB][2], auto mask_tag) {
         constexpr bool MASK = decltype(mask_tag)::value;
-        bf16x2 ones;
-        ones[0] = (__bf16)1.f;
-        ones[1] = (__bf16)1.f;
+        x2 ones;
+        ones[0] = (elem)1.f;
+        ones[1] = (elem)1.f;
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             float sum = 0.f;
@@ -386,10 +411,10 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
             for (int v = 0; v < 16; v += 2) {
                 const float e0 = fast_exp2(MASK ? sacc[qb][v] - m_ref[qb] : __builtin_fmaf(sacc[qb][v], c, -m_ref[qb]));
                 const float e1 = fast_exp2(MASK ? sacc[qb][v + 1] - m_ref[qb] : __builtin_fmaf(sacc[qb][v + 1], c, -m_ref[qb]));
-                bf16x2 pr;
-                pr[0] = (__bf16)e0;
-                pr[1] = (__bf16)e1;
-                sum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, sum, false);
+                x2 pr;
+                pr[0] = (elem)e0;
+                pr[1] = (elem)e1;
+                sum = E::dot2(pr, ones, sum);
                 pf[qb][v >> 3][v & 7] = pr[0];
                 pf[qb][v >> 3][(v & 7) + 1] = pr[1];
             }
@@ -409,9 +434,9 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
         settle(0, s_cur, Masked{});
     else
         settle(0, s_cur, Plain{});
-    bf16x8 kf[KSTEPS];  // K fragments of the next unit, fetched one iteration ahead
+    x8 kf[KSTEPS];  // K fragments of the next unit, fetched one iteration ahead
 #pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) kf[ks] = *(const bf16x8 *)(lds + (1 % NSLOT) * kSlotBytes + koff[ks]);
+    for (int ks = 0; ks < KSTEPS; ++ks) kf[ks] = *(const x8 *)(lds + (1 % NSLOT) * kSlotBytes + koff[ks]);
     {
         s16x4 raw[C::kFragsPerWave][2];
         transpose_load(0, raw);
@@ -455,34 +480,34 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
         const unsigned char *kt2 = lds + ((u + 2) % NSLOT) * kSlotBytes;
         const int entry = table_entry(u + PF);  // scalar load, consumed at the end of phase Y
 
-        bf16x8 pf[QB][2];
-        bf16x8 vfrag[2 * DB];
+        x8 pf[QB][2];
+        x8 vfrag[2 * DB];
         s16x4 raw[C::kFragsPerWave][2];
         float sum[QB];
-        bf16x2 ones;
-        ones[0] = (__bf16)1.f;
-        ones[1] = (__bf16)1.f;
+        x2 ones;
+        ones[0] = (elem)1.f;
+        ones[1] = (elem)1.f;
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) sum[qb] = 0.f;
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const int ks = g / QB, qb = g % QB;
-            nxt[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[qb][ks], ks == 0 ? zero : nxt[qb], 0, 0, 0);
+            nxt[qb] = E::mfma(kf[ks], qf[qb][ks], ks == 0 ? zero : nxt[qb]);
             {
                 const int v = 2 * (g / QB);
                 const float e0 = fast_exp2(CUR_MASK ? cur[qb][v] - m_ref[qb] : __builtin_fmaf(cur[qb][v], c, -m_ref[qb]));
                 const float e1 = fast_exp2(CUR_MASK ? cur[qb][v + 1] - m_ref[qb] : __builtin_fmaf(cur[qb][v + 1], c, -m_ref[qb]));
-                bf16x2 pr;
-                pr[0] = (__bf16)e0;
-                pr[1] = (__bf16)e1;
-                sum[qb] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, sum[qb], false);
+                x2 pr;
+                pr[0] = (elem)e0;
+                pr[1] = (elem)e1;
+                sum[qb] = E::dot2(pr, ones, sum[qb]);
                 pf[qb][v >> 3][v & 7] = pr[0];
                 pf[qb][v >> 3][(v & 7) + 1] = pr[1];
             }
             if (g * 8 / G != (g + 1) * 8 / G) {
                 const int f = g * 8 / G;
-                vfrag[f] = *(const bf16x8 *)(img + f * 1024);
+                vfrag[f] = *(const x8 *)(img + f * 1024);
             }
             if (g == 1) transpose_load(u + 1, raw);  // this wave's share of V(u+1), stored late in phase Y
             __builtin_amdgcn_sched_barrier(0);
@@ -498,7 +523,7 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const int f = g / QB, qb = g % QB;  // f = ks2 * DB + db
-            oacc[qb][f % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfrag[f], pf[qb][f / DB], oacc[qb][f % DB], 0, 0, 0);
+            oacc[qb][f % DB] = E::mfma(vfrag[f], pf[qb][f / DB], oacc[qb][f % DB]);
             const int sl = g - 2;  // the first two groups leave the last S MFMAs time to drain
             if (sl >= 0 && sl < 4 * QB) {
                 const int q2 = sl / 4, v0 = 4 * (sl % 4);
@@ -515,7 +540,7 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
             // K fragments of unit u+2, one per group (the fragments of u+1 were consumed in phase X)
             if (g * KSTEPS / G != (g + 1) * KSTEPS / G) {
                 const int ks = g * KSTEPS / G;
-                kf[ks] = *(const bf16x8 *)(kt2 + koff[ks]);
+                kf[ks] = *(const x8 *)(kt2 + koff[ks]);
             }
             if (g == G - 3) issue_unit(u + PF, entry);  // refill: unit u+PF replaces unit u+PF-NSLOT <= u
             if (g == G - 2) transpose_store(u + 1, raw);  // image (u+1)&1 was last read in iteration u-1
@@ -585,11 +610,11 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
         for (int db = 0; db < DB; ++db) {
 #pragma unroll
             for (int vq = 0; vq < 4; ++vq) {
-                bf16x2 a, b;
-                a[0] = (__bf16)(oacc[qb][db][4 * vq + 0] * inv);
-                a[1] = (__bf16)(oacc[qb][db][4 * vq + 1] * inv);
-                b[0] = (__bf16)(oacc[qb][db][4 * vq + 2] * inv);
-                b[1] = (__bf16)(oacc[qb][db][4 * vq + 3] * inv);
+                x2 a, b;
+                a[0] = (elem)(oacc[qb][db][4 * vq + 0] * inv);
+                a[1] = (elem)(oacc[qb][db][4 * vq + 1] * inv);
+                b[0] = (elem)(oacc[qb][db][4 * vq + 2] * inv);
+                b[1] = (elem)(oacc[qb][db][4 * vq + 3] * inv);
                 const int chunk = 4 * db + vq;  // 16-byte chunk of the row; lhalf selects its 8-byte half
                 u32x2 w;
                 w[0] = __builtin_bit_cast(uint32_t, a);
@@ -610,24 +635,24 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
     }
 }
 
-template <int QB, int HPW, int NSLOT, int PF, int WAVES>
+template <typename E, int QB, int HPW, int NSLOT, int PF, int WAVES>
 bool ring_valid(const KParams &p)
 {
-    return p.head_dim == kHD && p.group % HPW == 0;
+    return p.dtype == E::kDtype && p.head_dim == kHD && p.group % HPW == 0;
 }
 
-template <int QB, int HPW, int NSLOT, int PF, int WAVES, bool PAGED>
+template <typename E, int QB, int HPW, int NSLOT, int PF, int WAVES, bool PAGED>
 hipError_t ring_launch_impl(const KParams &p, hipStream_t stream, int64_t blocks)
 {
     using C = RingCfg<QB, HPW, NSLOT, PF, WAVES>;
-    auto kern = prefill_ring_kernel<QB, HPW, NSLOT, PF, WAVES, PAGED>;
+    auto kern = prefill_ring_kernel<E, QB, HPW, NSLOT, PF, WAVES, PAGED>;
     static hipError_t attr = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::kLdsBytes);
     if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(C::kThreads), C::kLdsBytes, stream, p);
     return hipGetLastError();
 }
 
-template <int QB, int HPW, int NSLOT, int PF, int WAVES, int ORDER>
+template <typename E, int QB, int HPW, int NSLOT, int PF, int WAVES, int ORDER>
 hipError_t ring_launch(const KParams &p_in, hipStream_t stream)
 {
     KParams p = p_in;
@@ -638,14 +663,25 @@ hipError_t ring_launch(const KParams &p_in, hipStream_t stream)
     const int64_t blocks = q_tiles * p.num_seqs * nhg;
     if (blocks <= 0) return hipSuccess;
     if (blocks > 0x7fffffff) return hipErrorInvalidConfiguration;
-    return p.block_table ? ring_launch_impl<QB, HPW, NSLOT, PF, WAVES, true>(p, stream, blocks)
-                         : ring_launch_impl<QB, HPW, NSLOT, PF, WAVES, false>(p, stream, blocks);
+    return p.block_table ? ring_launch_impl<E, QB, HPW, NSLOT, PF, WAVES, true>(p, stream, blocks)
+                         : ring_launch_impl<E, QB, HPW, NSLOT, PF, WAVES, false>(p, stream, blocks);
 }
 
-#define RING_ONE(QB, HPW, NSLOT, PF, WAVES, ORDER, TAG)                                                                  \
-    {                                                                                                                    \
-        "prefill_bf16_ring d128 qb" #QB " w" #WAVES " hpw" #HPW " slots" #NSLOT " pf" #PF TAG, WAVES * 32 * QB, kUnit,    \
-            WAVES, HPW, PF, 0, ring_valid<QB, HPW, NSLOT, PF, WAVES>, ring_launch<QB, HPW, NSLOT, PF, WAVES, ORDER>, ORDER \
+// This file is compiled twice: as it stands for bf16, and included by prefill_f16_ring.hip with
+// ATTN_RING_ELEM_F16 defined for fp16 inputs (a smaller set of instances).
+#ifdef ATTN_RING_ELEM_F16
+#define RING_ELEM ElemF16
+#define RING_NAME "prefill_f16_ring"
+#else
+#define RING_ELEM ElemBf16
+#define RING_NAME "prefill_bf16_ring"
+#endif
+
+#define RING_ONE(QB, HPW, NSLOT, PF, WAVES, ORDER, TAG)                                                            \
+    {                                                                                                              \
+        RING_NAME " d128 qb" #QB " w" #WAVES " hpw" #HPW " slots" #NSLOT " pf" #PF TAG, WAVES * 32 * QB, kUnit, WAVES, \
+            HPW, PF, 0, ring_valid<RING_ELEM, QB, HPW, NSLOT, PF, WAVES>,                                          \
+            ring_launch<RING_ELEM, QB, HPW, NSLOT, PF, WAVES, ORDER>, ORDER                                        \
     }
 // both grid orders of one compiled kernel
 #define RING_INSTANCE(QB, HPW, NSLOT, PF, WAVES) \
@@ -653,6 +689,18 @@ hipError_t ring_launch(const KParams &p_in, hipStream_t stream)
 
 }  // namespace
 
+#ifdef ATTN_RING_ELEM_F16
+const Instance *prefill_ring_f16_instances(int *count)
+{
+    static const Instance table[] = {
+        RING_INSTANCE(1, 4, 8, 5, 8), RING_INSTANCE(1, 2, 8, 5, 8), RING_INSTANCE(1, 1, 8, 5, 8),
+        RING_INSTANCE(1, 4, 8, 6, 8), RING_INSTANCE(1, 4, 4, 4, 4), RING_INSTANCE(1, 2, 4, 4, 4),
+        RING_INSTANCE(1, 1, 4, 4, 4),
+    };
+    *count = (int)(sizeof(table) / sizeof(table[0]));
+    return table;
+}
+#else
 const Instance *prefill_ring_instances(int *count)
 {
     static const Instance table[] = {
@@ -665,5 +713,6 @@ const Instance *prefill_ring_instances(int *count)
     *count = (int)(sizeof(table) / sizeof(table[0]));
     return table;
 }
+#endif
 
 }  // namespace attn

@@ -134,9 +134,8 @@ def test_empty_batch_and_error_codes_on_device():
     dw = DeviceWorkload(wl)
     a = dw.args(True)
     a.workspace_bytes = 16
-    for i in range(A.attn_num_instances(True)):
-        if "split256" in A.attn_instance_name(True, i) and "d128 w4" in A.attn_instance_name(True, i):
-            A.attn_force_instance(True, i)
+    names = [A.attn_instance_name(True, i) for i in range(A.attn_num_instances(True))]
+    A.attn_force_instance(True, names.index("decode_bf16 d128 w4 split256"))
     assert A.load_library().attn_decode_paged(a, None) == -5
     A.attn_force_instance(True, -1)
 

@@ -120,8 +120,9 @@ def test_in_place_output_zero_rows_large_values_and_errors():
     with pytest.raises(A.AttnError) as e:
         A.rmsnorm_fused_add(torch.zeros(2, 1001, dtype=torch.bfloat16, device="cuda"), w, torch.zeros(2, 1001, dtype=torch.bfloat16, device="cuda"), 1e-6)
     assert e.value.status == -4
-    with pytest.raises(TypeError):
+    with pytest.raises(A.AttnError) as e:  # only bf16 rows
         A.rmsnorm_fused_add(torch.zeros(2, 1024, dtype=torch.float16, device="cuda"), w, o, 1e-6)
+    assert e.value.status == -3
 
 
 def test_tune_records_a_winner_in_the_shared_cache_file(tmp_path):

@@ -169,6 +169,18 @@ def make_paged(seed, kind, q_lens, kv_lens, Hq, Hkv, D, block_size, num_blocks, 
                     block_size=block_size, meta={"kv_lens": kv_lens.tolist(), "num_blocks": num_blocks})
 
 
+def as_f16(wl: "Workload") -> "Workload":
+    """The same workload with q, k, v stored as IEEE fp16 (the bf16 values rounded to nearest even)."""
+    import copy
+
+    out = copy.copy(wl)
+    conv = lambda a: (bf16_bits_to_f32(a) if a.dtype == np.uint16 else a).astype(np.float16)
+    out.q, out.k, out.v = conv(wl.q), conv(wl.k), conv(wl.v)
+    out.dtype = "f16"
+    out.name = wl.name + "_f16"
+    return out
+
+
 # --- the five benchmark configurations ------------------------------------------------
 
 def config1(seed=1):
