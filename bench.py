@@ -297,7 +297,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", choices=sorted(WORKLOADS), default="c2")
+    ap.add_argument("--workload", choices=sorted(WORKLOADS) + ["rmsnorm"], default="c2",
+                    help="c2..c5: attention configurations (c2 is the headline); rmsnorm: only the fused RMS norm leg")
     ap.add_argument("--no-extra", action="store_true", help="skip the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-tune", action="store_true", help="keep the built-in heuristic (default: attn_tune runs first, untimed)")
@@ -322,6 +323,13 @@ def main():
         print(json.dumps({"copy_probe_bytes_read": 1 << 30, "copy_probe_bytes_written": 1 << 30, "copies": 3}))
         return
 
+    if a.workload == "rmsnorm":
+        r = measure_rmsnorm(a.steps, a.warmup, not a.no_tune)
+        print(json.dumps({"metric": r["metric"], "value": r["value"], "unit": r["unit"], "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+                          "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+                          "dtype": "bf16", "data": "synthetic", "config": {"workload": r["workload"], "instance": r["instance"]},
+                          "kernel_ms_mean": r["kernel_ms_mean"], "roofline": r["roofline"]}), flush=True)
+        return
     wl, main_res = measure(WORKLOADS[a.workload], a.steps, a.warmup, not a.no_tune)
     line = {
         "metric": main_res["metric"], "value": main_res["value"], "unit": main_res["unit"], "n_gpus": 1,
