@@ -35,10 +35,11 @@ WORKLOADS = {"c2": 2, "c3": 3, "c4": 4, "c5": 5}
 # commands are in profiles/hbm_traffic_all_workloads_pmc.md.  Keyed by workload and kernel family:
 # a run that selects another family reports null.
 MEASURED_TRAFFIC_BYTES = {
-    ("c2_decode_8b", "decode_bf16_balanced"): (2 * (311776 + 2658) + 4992 + 512) * 1024,
-    ("c5_decode_70b_long", "decode_bf16_balanced"): (2 * (757321 + 4460) + 8700 + 256) * 1024,
-    ("c3_prefill_8b", "prefill_bf16_ring"): (2 * 101256 + 70104) * 1024,
-    ("c4_chunked_prefill", "prefill_bf16_ring seqmajor"): (2 * 213641 + 65536) * 1024,
+    ("c2_decode_8b", "decode_bf16_balanced"): (2 * (311784 + 2814) + 4993 + 512) * 1024,
+    ("c5_decode_70b_long", "decode_bf16_balanced"): (2 * (757309 + 4864) + 8700 + 256) * 1024,
+    ("c3_prefill_8b", "prefill_bf16_ring"): (2 * 92097 + 70104) * 1024,
+    ("c4_chunked_prefill", "prefill_bf16_ring seqmajor"): (2 * 213321 + 65536) * 1024,
+    ("rmsnorm_8b_t8192_h4096", "rmsnorm_bf16"): (2 * 65653 + 131072) * 1024,
 }
 
 
@@ -249,7 +250,7 @@ def measure_rmsnorm(steps: int, warmup: int, tune: bool):
             "value": nbytes / (wall_ms * 1e-3) / 1e9, "ms_per_step": wall_ms, "kernel_ms_mean": ev_ms, "algorithmic_bytes": nbytes,
             "timed_as": "one HIP graph of all steps",
             "roofline": {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBPS,
-                         "traffic": None}}
+                         "traffic": _traffic(wl.name, inst)}}
 
 
 def cpu_baseline(wl, unit: str):

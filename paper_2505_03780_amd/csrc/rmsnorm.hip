@@ -211,16 +211,20 @@ std::string bucket_key(const rmsnorm_args *a)
     return buf;
 }
 
-// Built-in choice: with many rows, a wavefront (or two) per row and several rows per workgroup keep
-// the reduction inside the wavefront; with few rows, more lanes per row put more compute units to work.
+// Built-in choice, from a sweep over hidden sizes 1024..8192 and 16..32768 rows: the fewest vectors
+// per lane (the row spread over as many lanes as it has 16-byte vectors, up to 1024) wins or ties
+// everywhere; among those the narrowest workgroup that covers the row, with the most rows.
 int heuristic(const rmsnorm_args *a)
 {
-    const int want_tpr = a->num_tokens >= 2048 ? (a->hidden > 4096 ? 128 : 64) : (a->hidden >= 4096 ? 512 : 256);
     int best = -1;
     for (int i = 0; i < kNumInstances; ++i) {
         if (!rms_valid(kInstances[i], a->hidden)) continue;
-        if (best < 0) best = i;
-        if (kInstances[i].tpr == want_tpr && (kInstances[best].tpr != want_tpr || kInstances[i].rows > kInstances[best].rows)) best = i;
+        if (best < 0) {
+            best = i;
+            continue;
+        }
+        const RmsInstance &c = kInstances[i], &b = kInstances[best];
+        if (c.vpt < b.vpt || (c.vpt == b.vpt && (c.tpr < b.tpr || (c.tpr == b.tpr && c.rows > b.rows)))) best = i;
     }
     return best;
 }
