@@ -27,7 +27,10 @@
  *  - Errors that the host can see are returned as a negative attn_status and
  *    nothing is enqueued.  Out-of-range block_table entries, or seq_lens /
  *    query_start_loc that disagree with total_q, max_q_len, max_kv_len, are
- *    undefined behaviour.
+ *    undefined behaviour -- unless ATTN_DEBUG_VALIDATE=1 is set in the environment:
+ *    then every hot call first drains the stream, copies these integers to the
+ *    host and returns ATTN_ERR_SHAPE if they are inconsistent (a debugging mode:
+ *    synchronous, not capturable).
  *  - Hot calls are re-entrant; the winner cache is guarded by a mutex.
  */
 #ifndef ATTN_H_

@@ -403,11 +403,59 @@ size_t decode_workspace_bytes(int num_seqs, int num_q_heads, int head_dim, int m
     return std::max(fixed, balanced_workspace_bytes(num_seqs, num_q_heads, head_dim, kMaxBalancedWgs));
 }
 
+// Debug aid, switched on by ATTN_DEBUG_VALIDATE=1 in the environment: the device-side integers that
+// the hot call otherwise trusts are copied to the host (the stream is drained first, so the call
+// is neither asynchronous nor capturable in this mode) and checked against the host-side bounds.
+int debug_validate_device_side(const attn_args *a, int is_decode, hipStream_t stream)
+{
+    const int B = a->num_seqs;
+    if (hipStreamSynchronize(stream) != hipSuccess) return ATTN_ERR_HIP;
+    std::vector<int32_t> lens(B), qsl(B + 1, 0), kvsl;
+    if (hipMemcpy(lens.data(), a->seq_lens, B * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess) return ATTN_ERR_HIP;
+    if (!is_decode && hipMemcpy(qsl.data(), a->query_start_loc, (B + 1) * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess)
+        return ATTN_ERR_HIP;
+    if (is_decode)
+        for (int s = 0; s <= B; ++s) qsl[s] = s;
+    if (qsl[0] != 0 || qsl[B] != a->total_q) return ATTN_ERR_SHAPE;
+    for (int s = 0; s < B; ++s) {
+        const int nq = qsl[s + 1] - qsl[s];
+        if (nq < 0 || nq > a->max_q_len || lens[s] < 0 || lens[s] > a->max_kv_len) return ATTN_ERR_SHAPE;
+        if (a->causal && nq > lens[s]) return ATTN_ERR_SHAPE;  // a query positioned before key 0
+    }
+    if (a->block_table) {
+        std::vector<int32_t> row(a->block_table_stride);
+        for (int s = 0; s < B; ++s) {
+            const int need = (lens[s] + a->block_size - 1) / a->block_size;
+            if (need > a->block_table_stride) return ATTN_ERR_SHAPE;
+            if (hipMemcpy(row.data(), a->block_table + (size_t)s * a->block_table_stride, (size_t)need * sizeof(int32_t),
+                          hipMemcpyDeviceToHost) != hipSuccess)
+                return ATTN_ERR_HIP;
+            for (int b = 0; b < need; ++b)
+                if (row[b] < 0 || row[b] >= a->num_blocks) return ATTN_ERR_SHAPE;
+        }
+    } else {
+        const int32_t *src = a->kv_start_loc ? a->kv_start_loc : a->query_start_loc;
+        kvsl.resize(B + 1);
+        if (hipMemcpy(kvsl.data(), src, (B + 1) * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess) return ATTN_ERR_HIP;
+        for (int s = 0; s < B; ++s)
+            if (kvsl[s] < 0 || kvsl[s + 1] < kvsl[s] || kvsl[s] + lens[s] > kvsl[s + 1]) return ATTN_ERR_SHAPE;
+    }
+    return ATTN_OK;
+}
+
 int run(const attn_args *a, int is_decode, hipStream_t stream, int instance_override)
 {
     int rc = validate(a, is_decode);
     if (rc != ATTN_OK) return rc;
     if (a->num_seqs == 0 || a->total_q == 0) return ATTN_OK;
+    const char *dbg = getenv("ATTN_DEBUG_VALIDATE");
+    if (dbg && dbg[0] == '1') {
+        rc = debug_validate_device_side(a, is_decode, stream);
+        if (rc != ATTN_OK) {
+            (void)hipGetLastError();
+            return rc;
+        }
+    }
     KParams p = to_kparams(a, is_decode);
     if (a->dtype == ATTN_F32) {
         return launch_prefill_f32(p, stream) == hipSuccess ? ATTN_OK : ATTN_ERR_HIP;

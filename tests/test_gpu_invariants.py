@@ -159,3 +159,35 @@ def test_graph_capture_and_replay_matches_eager():
         g.replay()
         torch.cuda.synchronize()
         assert np.array_equal(eager, _bits(dw.out))
+
+
+def test_debug_validate_catches_bad_device_side_integers(monkeypatch):
+    wl = W.make_paged(61, "decode", np.ones(3, np.int32), [100, 40, 257], 32, 8, 128, 16, 64)
+    dw = DeviceWorkload(wl)
+    lib = A.load_library()
+    monkeypatch.setenv("ATTN_DEBUG_VALIDATE", "1")
+    a = dw.args(True)
+    assert lib.attn_decode_paged(a, None) == 0  # consistent inputs pass
+    good = int(dw.bt[1, 0])
+    dw.bt[1, 0] = 64  # one past the pool
+    assert lib.attn_decode_paged(a, None) == -2
+    dw.bt[1, 0] = -1
+    assert lib.attn_decode_paged(a, None) == -2
+    dw.bt[1, 0] = good
+    dw.bt[1, 5] = 10 ** 6  # past ceil(40 / 16) entries: never read, never checked
+    assert lib.attn_decode_paged(a, None) == 0
+    keep = int(dw.seq_lens[2])
+    dw.seq_lens[2] = dw.max_kv + 1  # longer than the host was told
+    assert lib.attn_decode_paged(a, None) == -2
+    dw.seq_lens[2] = keep
+    # prefill: query_start_loc that disagrees with total_q, and a chunk longer than max_q_len
+    pw = W.make_prefill_contiguous(62, [33, 70], 8, 2, 128)
+    dp = DeviceWorkload(pw)
+    b = dp.args(False)
+    assert lib.attn_prefill_varlen(b, None) == 0
+    b.total_q -= 1
+    assert lib.attn_prefill_varlen(b, None) == -2
+    b.total_q += 1
+    b.max_q_len = 64
+    assert lib.attn_prefill_varlen(b, None) == -2
+    torch.cuda.synchronize()
