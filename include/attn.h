@@ -168,7 +168,8 @@ size_t attn_workspace_bytes(const attn_args *args, int is_decode);
  * launches of every valid instance, iters/2 of the best third (the built-in
  * choice and the winners already known for neighbouring buckets always stay in),
  * `iters` (<= 0: a default) of the best three; an instance three times slower
- * than the best so far is dropped after one launch.  The call records the
+ * than the best so far is dropped after one launch; the built-in choice wins
+ * ties within 2 % (launch-to-launch noise).  The call records the
  * fastest instance and, if cache_path is not NULL, merges it into that file
  * (atomic replace).  Synchronous; not capturable.
  * flags: bit 0 = print one line per measurement to stderr; bit 1 = exhaustive
