@@ -653,7 +653,9 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void decode_balanced_kernel(
         if (n > 0) {
             const int k_lo = off * kChunk;
             const int k_hi = (off + n) * kChunk < n_kv ? (off + n) * kChunk : n_kv;
-            float *partial = p.workspace + (int64_t)(w + s) * p.num_q_heads * (HD + 2);
+            // a sequence that lies inside this walk is finished here; a piece of a sequence shared with
+            // other workgroups leaves a record for the merge kernel
+            float *partial = n == nc ? nullptr : p.workspace + (int64_t)(w + s) * p.num_q_heads * (HD + 2);
             decode_stream_part<HD, WAVES>(p, lds + wave * C::kVBytes, lane, s, kvh, n_kv, k_lo, k_hi, partial, HD + 2);
             remaining -= n;
         }
@@ -664,16 +666,19 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void decode_balanced_kernel(
 
 // Combine for the token-balanced variant: the pieces of sequence s are the workgroups that overlap its
 // chunk range, at record indices workgroup + s.  One wavefront per (sequence, KV head, pair of query heads).
+constexpr int kMergeWaves = 4;  // (sequence, KV head, head pair) units per merge workgroup
+
 template <int HD>
-__global__ __launch_bounds__(64) void decode_balanced_combine_kernel(const KParams p)
+__global__ __launch_bounds__(64 * kMergeWaves) void decode_balanced_combine_kernel(const KParams p)
 {
     const int pairs = (p.group + 1) / 2;
-    int bid = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    int bid = blockIdx.x * kMergeWaves + (threadIdx.x >> 6);
+    if (bid >= p.num_seqs * p.num_kv_heads * pairs) return;
     const int pair = bid % pairs;
     bid /= pairs;
     const int kvh = bid % p.num_kv_heads;
     const int s = bid / p.num_kv_heads;
-    const int lane = threadIdx.x;
     const int num_wgs = p.num_splits;
     const int B = p.num_seqs;
     const int32_t *prefix = (const int32_t *)(p.workspace + (int64_t)(num_wgs + B) * p.num_q_heads * (HD + 2));
@@ -682,6 +687,7 @@ __global__ __launch_bounds__(64) void decode_balanced_combine_kernel(const KPara
     // an empty context has no piece: parts = 0 makes the merge write zeros
     const int w0 = c1 > c0 ? c0 / per_wg : 0;
     const int parts = c1 > c0 ? (c1 - 1) / per_wg - w0 + 1 : 0;
+    if (parts == 1) return;  // the main kernel wrote this sequence itself
     const int64_t stride = (int64_t)p.num_q_heads * (HD + 2);
     merge_pair<HD>(p, lane, s, kvh, pair, p.workspace + (int64_t)(w0 + s) * stride + (int64_t)kvh * p.group * (HD + 2), parts, HD + 2, stride);
 }
@@ -689,15 +695,16 @@ __global__ __launch_bounds__(64) void decode_balanced_combine_kernel(const KPara
 // Combine for the fixed-split kernels, one wavefront per (sequence, KV head, pair of query heads): records are laid out
 // [sequence][head][part].  Parts that hold no key were never written and are not read.
 template <int HD>
-__global__ __launch_bounds__(64) void decode_combine_kernel(const KParams p)
+__global__ __launch_bounds__(64 * kMergeWaves) void decode_combine_kernel(const KParams p)
 {
     const int pairs = (p.group + 1) / 2;
-    int bid = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    int bid = blockIdx.x * kMergeWaves + (threadIdx.x >> 6);
+    if (bid >= p.num_seqs * p.num_kv_heads * pairs) return;
     const int pair = bid % pairs;
     bid /= pairs;
     const int kvh = bid % p.num_kv_heads;
     const int s = bid / p.num_kv_heads;
-    const int lane = threadIdx.x;
     const int n_kv = p.seq_lens[s];
     int parts = (n_kv + p.split_len - 1) / p.split_len;
     parts = parts < 1 ? 1 : parts;  // part 0 is always written (m = -inf, l = 0 for an empty context)
@@ -746,7 +753,9 @@ hipError_t decode_balanced_launch(const KParams &p, hipStream_t stream)
     hipLaunchKernelGGL((decode_balanced_kernel<HD, WAVES>), dim3((unsigned)blocks), dim3(WAVES * 64), 0, stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(decode_balanced_combine_kernel<HD>, dim3((unsigned)(p.num_seqs * p.num_kv_heads * ((p.group + 1) / 2))), dim3(64), 0, stream, p);
+    const int64_t units = (int64_t)p.num_seqs * p.num_kv_heads * ((p.group + 1) / 2);
+    hipLaunchKernelGGL(decode_balanced_combine_kernel<HD>, dim3((unsigned)((units + kMergeWaves - 1) / kMergeWaves)), dim3(64 * kMergeWaves), 0,
+                       stream, p);
     return hipGetLastError();
 }
 
@@ -774,13 +783,13 @@ hipError_t decode_balanced_launch(const KParams &p, hipStream_t stream)
 #ifdef ATTN_DECODE_ELEM_F16
 hipError_t launch_decode_combine_f16(const KParams &p, hipStream_t stream)
 {
-    const int64_t blocks = (int64_t)p.num_seqs * p.num_kv_heads * ((p.group + 1) / 2);
+    const int64_t blocks = ((int64_t)p.num_seqs * p.num_kv_heads * ((p.group + 1) / 2) + kMergeWaves - 1) / kMergeWaves;
     if (blocks <= 0) return hipSuccess;
     if (blocks > 0x7fffffff) return hipErrorInvalidConfiguration;
     if (p.head_dim == 128)
-        hipLaunchKernelGGL(decode_combine_kernel<128>, dim3((unsigned)blocks), dim3(64), 0, stream, p);
+        hipLaunchKernelGGL(decode_combine_kernel<128>, dim3((unsigned)blocks), dim3(64 * kMergeWaves), 0, stream, p);
     else if (p.head_dim == 64)
-        hipLaunchKernelGGL(decode_combine_kernel<64>, dim3((unsigned)blocks), dim3(64), 0, stream, p);
+        hipLaunchKernelGGL(decode_combine_kernel<64>, dim3((unsigned)blocks), dim3(64 * kMergeWaves), 0, stream, p);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();
@@ -802,13 +811,13 @@ const Instance *decode_f16_instances(int *count)
 #else
 hipError_t launch_decode_combine(const KParams &p, hipStream_t stream)
 {
-    const int64_t blocks = (int64_t)p.num_seqs * p.num_kv_heads * ((p.group + 1) / 2);
+    const int64_t blocks = ((int64_t)p.num_seqs * p.num_kv_heads * ((p.group + 1) / 2) + kMergeWaves - 1) / kMergeWaves;
     if (blocks <= 0) return hipSuccess;
     if (blocks > 0x7fffffff) return hipErrorInvalidConfiguration;
     if (p.head_dim == 128)
-        hipLaunchKernelGGL(decode_combine_kernel<128>, dim3((unsigned)blocks), dim3(64), 0, stream, p);
+        hipLaunchKernelGGL(decode_combine_kernel<128>, dim3((unsigned)blocks), dim3(64 * kMergeWaves), 0, stream, p);
     else if (p.head_dim == 64)
-        hipLaunchKernelGGL(decode_combine_kernel<64>, dim3((unsigned)blocks), dim3(64), 0, stream, p);
+        hipLaunchKernelGGL(decode_combine_kernel<64>, dim3((unsigned)blocks), dim3(64 * kMergeWaves), 0, stream, p);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();
