@@ -95,6 +95,20 @@ def test_paged_block_sizes(bs):
     check_full(wl)
     wl = W.make_paged(33, "decode", [1, 1, 1], [1, 77, 600], 8, 2, 128, bs, 64)
     check_full(wl)
+    # every decode and prefill instance, with eight KV heads so that all kernel families apply
+    wl = W.make_paged(34, "decode", [1, 1, 1, 1], [1, 77, 600, 129], 32, 8, 128, bs, 64)
+    dw = DeviceWorkload(wl)
+    ref = oracle.attention(oracle_problem(wl))
+    for i in _valid_instances(dw, True):
+        A.attn_force_instance(True, i)
+        assert_close(to_host_f64(dw.run(True)), ref, "bf16", "bs %d %s" % (bs, A.attn_instance_name(True, i)))
+    A.attn_force_instance(True, -1)
+    wl = _chunked(35, [40, 70, 1], [100, 333, 65], Hq=32, Hkv=8, bs=bs)
+    dw = DeviceWorkload(wl)
+    ref = oracle.attention(oracle_problem(wl))
+    for i in _valid_instances(dw, False):
+        A.attn_force_instance(False, i)
+        assert_close(to_host_f64(dw.run(False)), ref, "bf16", "bs %d %s" % (bs, A.attn_instance_name(False, i)))
 
 
 DECODE_LENS = [1, 15, 16, 17, 31, 32, 33, 100, 255, 256, 257, 700, 1500]
