@@ -572,13 +572,100 @@ __device__ __forceinline__ void merge_pair(const KParams &p, int lane, int s, in
     merge_head<HD>(rec + (int64_t)hc * head_stride, parts, part_stride, lane, o);
 }
 
+// Where a workgroup's run of chunks starts, for the token-balanced kernels: the batch's 32-key chunks
+// laid end to end are cut into num_wgs equal runs; run w is [x0, x1) and starts `off` chunks into
+// sequence `s`.  Every wavefront works this out on its own (no barrier): lane l sums the chunk counts
+// of a contiguous block of ceil(B / 64) sequences (independent loads, no cross-lane step inside the
+// loop), one 64-wide scan gives the block prefix sums, and a second 64-wide scan over the one block
+// that holds x0 finds the sequence.  Batches beyond 4096 sequences take a loop of 64-wide scans.
+// The writer wavefront also stores the per-sequence chunk prefix sums for the merge kernel.
+struct RunStart {
+    int total, x0, x1, s, off;
+};
+__device__ __forceinline__ RunStart locate_run(const KParams &p, int lane, int w, int num_wgs, bool writer, int32_t *prefix_out)
+{
+    const int B = p.num_seqs;
+    RunStart r{0, 0, 0, 0, 0};
+    auto scan64 = [&](int v) {
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(v, o);
+            if (lane >= o) v += t;
+        }
+        return v;
+    };
+    if (B <= 4096) {
+        const int R = (B + 63) / 64;  // sequences per lane
+        int mine = 0;
+#pragma unroll 8
+        for (int k = 0; k < R; ++k) {  // unrolled so that the loads of a batch are in flight together
+            const int i = lane * R + k;
+            mine += i < B ? (p.seq_lens[i] + kChunk - 1) / kChunk : 0;
+        }
+        const int incl = scan64(mine);
+        r.total = __builtin_amdgcn_readlane(incl, 63);
+        if (writer) {
+            int run = incl - mine;
+            for (int k = 0; k < R; ++k) {
+                const int i = lane * R + k;
+                if (i < B) {
+                    prefix_out[i] = run;
+                    run += (p.seq_lens[i] + kChunk - 1) / kChunk;
+                }
+            }
+            if (lane == 0) prefix_out[B] = r.total;
+        }
+        const int per_wg = (r.total + num_wgs - 1) / num_wgs;
+        r.x0 = w * per_wg;
+        r.x1 = r.x0 + per_wg < r.total ? r.x0 + per_wg : r.total;
+        if (r.x0 >= r.x1) return r;
+        // the block (lane) that holds chunk x0, then the sequence inside the block
+        const int blk = __builtin_ctzll(__builtin_amdgcn_ballot_w64(incl > r.x0));
+        const int base = __builtin_amdgcn_readlane(incl - mine, blk);
+        const int i2 = blk * R + lane;
+        const int c2 = (lane < R && i2 < B) ? (p.seq_lens[i2] + kChunk - 1) / kChunk : 0;
+        const int incl2 = scan64(c2);
+        const int j = __builtin_ctzll(__builtin_amdgcn_ballot_w64(base + incl2 > r.x0));
+        r.s = blk * R + j;
+        r.off = r.x0 - (base + __builtin_amdgcn_readlane(incl2 - c2, j));
+        return r;
+    }
+    for (int g0 = 0; g0 < B; g0 += 64) {
+        const int i = g0 + lane;
+        const int c = i < B ? (p.seq_lens[i] + kChunk - 1) / kChunk : 0;
+        const int incl = scan64(c);
+        if (writer && i < B) prefix_out[i] = r.total + incl - c;
+        r.total += __builtin_amdgcn_readlane(incl, 63);
+    }
+    if (writer && lane == 0) prefix_out[B] = r.total;
+    const int per_wg = (r.total + num_wgs - 1) / num_wgs;
+    r.x0 = w * per_wg;
+    r.x1 = r.x0 + per_wg < r.total ? r.x0 + per_wg : r.total;
+    if (r.x0 >= r.x1) return r;
+    int base = 0;
+    for (int g0 = 0; g0 < B; g0 += 64) {
+        const int i = g0 + lane;
+        const int c = i < B ? (p.seq_lens[i] + kChunk - 1) / kChunk : 0;
+        const int incl = scan64(c);
+        const int grp = __builtin_amdgcn_readlane(incl, 63);
+        if (r.x0 < base + grp) {
+            const int idx = __builtin_ctzll(__builtin_amdgcn_ballot_w64(base + incl > r.x0));
+            r.s = g0 + idx;
+            r.off = r.x0 - (base + __builtin_amdgcn_readlane(incl - c, idx));
+            break;
+        }
+        base += grp;
+    }
+    return r;
+}
+
 // Token-balanced variant: the key axis of the whole batch, cut into 32-key chunks and laid end to
 // end, is divided evenly over the workgroups (one per compute unit and KV-head block), whatever the
 // mix of sequence lengths.  A workgroup therefore walks a run of chunks that may start in the middle
 // of one sequence and end in the middle of another; every (workgroup, sequence) piece leaves one
 // partial record with the unique index  workgroup + sequence  (both only grow along the walk).  The
-// chunk prefix sums of the batch are recomputed by every wavefront (a 64-wide scan over seq_lens) and
-// written once for the combine kernel.
+// chunk prefix sums of the batch are recomputed by every wavefront (locate_run) and written once for
+// the combine kernel.
 //   workspace: [num_wgs + num_seqs][Hq][HD + 2] floats, then int32 chunk prefix sums [num_seqs + 1].
 template <int HD, int WAVES>
 __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void decode_balanced_kernel(const KParams p)
@@ -596,53 +683,10 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void decode_balanced_kernel(
     int32_t *prefix_out = (int32_t *)(p.workspace + (int64_t)(num_wgs + B) * p.num_q_heads * (HD + 2));
     const bool writer = blockIdx.x == 0 && wave == 0;
 
-    // pass 1: total number of chunks (every wavefront on its own: no barrier in this kernel)
-    int total = 0;
-    for (int g0 = 0; g0 < B; g0 += 64) {
-        const int i = g0 + lane;
-        int c = i < B ? (p.seq_lens[i] + kChunk - 1) / kChunk : 0;
-        int incl = c;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int t = __shfl_up(incl, o);
-            if (lane >= o) incl += t;
-        }
-        if (writer && i < B) prefix_out[i] = total + incl - c;
-        total += __builtin_amdgcn_readlane(incl, 63);
-    }
-    if (writer && lane == 0) prefix_out[B] = total;
-    if (kvh >= p.num_kv_heads) return;
-    const int per_wg = (total + num_wgs - 1) / num_wgs;
-    const int x0 = w * per_wg;
-    int x1 = x0 + per_wg < total ? x0 + per_wg : total;
-    if (x0 >= x1) return;
-
-    // pass 2: the sequence that holds chunk x0, and the offset of x0 inside it
-    int s = 0, off = 0;
-    {
-        int base = 0;
-        for (int g0 = 0; g0 < B; g0 += 64) {
-            const int i = g0 + lane;
-            const int c = i < B ? (p.seq_lens[i] + kChunk - 1) / kChunk : 0;
-            int incl = c;
-#pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
-                const int t = __shfl_up(incl, o);
-                if (lane >= o) incl += t;
-            }
-            const int grp = __builtin_amdgcn_readlane(incl, 63);
-            if (x0 < base + grp) {
-                // first lane whose inclusive prefix exceeds x0
-                const unsigned long long m = __builtin_amdgcn_ballot_w64(base + incl > x0);
-                const int idx = __builtin_ctzll(m);
-                const int excl = __builtin_amdgcn_readlane(incl - c, idx);
-                s = g0 + idx;
-                off = x0 - (base + excl);
-                break;
-            }
-            base += grp;
-        }
-    }
+    const RunStart run = locate_run(p, lane, w, num_wgs, writer, prefix_out);
+    if (kvh >= p.num_kv_heads || run.x0 >= run.x1) return;
+    const int x0 = run.x0, x1 = run.x1;
+    int s = run.s, off = run.off;
 
     // walk the pieces
     int remaining = x1 - x0;
@@ -762,10 +806,9 @@ hipError_t decode_balanced_launch(const KParams &p, hipStream_t stream)
 // SPLIT < 0 marks the token-balanced variant with -SPLIT workgroups per compute unit
 #define DECODE_BAL_INSTANCE(HD, WAVES, PER_CU)                                                                  \
     {                                                                                                          \
-        DECODE_NAME "_balanced d" #HD " w" #WAVES " percu" #PER_CU, 16, kChunk, WAVES, 16, 2, -PER_CU,            \
-            decode_valid<HD, WAVES>, decode_balanced_launch<HD, WAVES>                                         \
+        DECODE_NAME "_balanced d" #HD " w" #WAVES " percu" #PER_CU, 16, kChunk, WAVES, 16, 2, -PER_CU,           \
+            decode_valid<HD, WAVES>, decode_balanced_launch<HD, WAVES>                                  \
     }
-
 #define DECODE_SEQ_INSTANCE(HD, WAVES, SPLIT)                                                                  \
     {                                                                                                          \
         DECODE_NAME "_seq d" #HD " w" #WAVES " split" #SPLIT, 16, kChunk, WAVES, 16, 2, SPLIT, decode_valid<HD, WAVES>, \
