@@ -204,3 +204,21 @@ def test_config5_decode_70b_long_full_size():
     name = A.attn_instance_name(True, A.attn_selected_instance(a, True))
     assert "split0" not in name, "long contexts must take the split-K path, got " + name
     check_sampled(wl, 16 * 64, seed=5, dw=dw)
+
+
+@pytest.mark.parametrize("B", [333, 4200])
+def test_decode_large_batches_of_short_contexts(B):
+    """Many sequences per workgroup run: both ways of taking the chunk prefix sums (up to 4096
+    sequences one block per lane, beyond that a loop over the batch), a few empty contexts' worth of
+    one-key sequences, every token-balanced instance."""
+    rng = np.random.default_rng(B)
+    lens = rng.integers(1, 70, size=B).astype(np.int32)
+    lens[::17] = 1
+    wl = W.make_paged(50 + B, "decode", np.ones(B, np.int32), lens, 8, 4, 128, 16, int(np.sum((lens + 15) // 16)) + 3)
+    dw = DeviceWorkload(wl)
+    ref = oracle.attention(oracle_problem(wl))
+    ids = [i for i in _valid_instances(dw, True) if "balanced" in A.attn_instance_name(True, i)]
+    assert ids
+    for i in ids:
+        A.attn_force_instance(True, i)
+        assert_close(to_host_f64(dw.run(True)), ref, "bf16", "B %d %s" % (B, A.attn_instance_name(True, i)))
