@@ -202,6 +202,18 @@ int attn_selected_instance(const attn_args *args, int is_decode);
  * combinations are rejected by the hot call with ATTN_ERR_UNSUPPORTED. */
 void attn_force_instance(int is_decode, int id);
 
+/*
+ * Measurement aids (not part of the paper's method): what the device sustains for the two resources
+ * that bound the path, for quoting a result against the achievable next to the published peak.
+ * attn_probe_hbm_read enqueues a streaming read of `bytes` bytes (16-byte aligned device buffer,
+ * at least 16 bytes); `sink4` is a 4-byte device word that the kernel may touch.  attn_probe_mfma_bf16
+ * enqueues `iters` rounds of four independent 32x32x16 bf16 MFMAs on eight wavefronts per compute
+ * unit and returns the number of floating-point operations enqueued (> 0), or a negative attn_status.
+ * The caller times them on its stream.
+ */
+int attn_probe_hbm_read(const void *buf, size_t bytes, void *sink4, void *hip_stream);
+int64_t attn_probe_mfma_bf16(int iters, void *sink4, void *hip_stream);
+
 const char *attn_status_string(int status);
 
 #ifdef __cplusplus

@@ -1,0 +1,79 @@
+// Measurement aids: what this machine actually sustains for the two resources the attention path is
+// bounded by, so that a benchmark can quote its figures against the published peaks and against
+// these.  Not part of the method: a streaming read of a buffer (HBM) and a loop of independent
+// 32x32x16 bf16 MFMAs (matrix pipe).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/attn.h"
+
+namespace attn {
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// every lane reads 16 bytes per step, the grid strides over the buffer; the xor of everything read
+// goes out so that the loads cannot be dropped
+__global__ __launch_bounds__(256) void hbm_read_kernel(const u32x4 *src, size_t n_vec, uint32_t *sink)
+{
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+#pragma unroll 8
+    for (; i < n_vec; i += stride) acc ^= src[i];  // eight loads in flight per lane
+    const uint32_t x = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+    if (x == 0x9e3779b9u) atomicXor(sink, x);  // practically never taken; keeps the chain alive
+}
+
+// four independent accumulator chains per wavefront, `iters` rounds of four MFMAs each
+__global__ __launch_bounds__(512) void mfma_bf16_kernel(int iters, float *sink)
+{
+    bf16x8 a, b;
+    for (int e = 0; e < 8; ++e) {
+        a[e] = (__bf16)(float)((threadIdx.x + e) & 3);
+        b[e] = (__bf16)0.5f;
+    }
+    f32x16 c0 = {}, c1 = {}, c2 = {}, c3 = {};
+    for (int i = 0; i < iters; ++i) {
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c1, 0, 0, 0);
+        c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c2, 0, 0, 0);
+        c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c3, 0, 0, 0);
+    }
+    const float x = c0[0] + c1[1] + c2[2] + c3[3];
+    if (x == -1.f) sink[0] = x;  // never true (all products are non-negative)
+}
+
+}  // namespace
+}  // namespace attn
+
+extern "C" int attn_probe_hbm_read(const void *buf, size_t bytes, void *sink4, void *hip_stream)
+{
+    using namespace attn;
+    if (!buf || !sink4) return ATTN_ERR_NULL;
+    if (bytes < 16 || ((uintptr_t)buf & 15) || ((uintptr_t)sink4 & 3)) return ATTN_ERR_SHAPE;
+    const size_t n_vec = bytes / 16;
+    int dev = 0, cus = 256;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) cus = prop.multiProcessorCount;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(hbm_read_kernel, dim3((unsigned)(cus * 8)), dim3(256), 0, (hipStream_t)hip_stream, (const u32x4 *)buf, n_vec, (uint32_t *)sink4);
+    return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_ERR_HIP;
+}
+
+extern "C" int64_t attn_probe_mfma_bf16(int iters, void *sink4, void *hip_stream)
+{
+    using namespace attn;
+    if (!sink4) return ATTN_ERR_NULL;
+    if (iters <= 0 || iters > (1 << 24)) return ATTN_ERR_SHAPE;
+    int dev = 0, cus = 256;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) cus = prop.multiProcessorCount;
+    (void)hipGetLastError();
+    // one workgroup of eight wavefronts per compute unit: two wavefronts per SIMD
+    hipLaunchKernelGGL(mfma_bf16_kernel, dim3((unsigned)cus), dim3(512), 0, (hipStream_t)hip_stream, iters, (float *)sink4);
+    if (hipGetLastError() != hipSuccess) return ATTN_ERR_HIP;
+    return (int64_t)cus * 8 * (int64_t)iters * 4 * 32768;  // floating-point operations enqueued
+}

@@ -191,3 +191,13 @@ def test_debug_validate_catches_bad_device_side_integers(monkeypatch):
     b.max_q_len = 64
     assert lib.attn_prefill_varlen(b, None) == -2
     torch.cuda.synchronize()
+
+
+def test_probes_report_plausible_sustained_rates():
+    r = A.probe_achievable(read_bytes=1 << 29, mfma_iters=1 << 12)
+    # an MI355X sustains several TB/s and more than a PFLOP/s; far looser bounds catch a broken probe
+    assert 1000.0 < r["hbm_read_GBps"] < 8000.0, r
+    assert 300.0 < r["mfma_bf16_TFLOPs"] < 2600.0, r
+    lib = A.load_library()
+    assert lib.attn_probe_hbm_read(None, 64, None, None) == -1
+    assert lib.attn_probe_mfma_bf16(0, 0x1000, None) == -2
