@@ -27,23 +27,37 @@ __global__ __launch_bounds__(256) void hbm_read_kernel(const u32x4 *src, size_t 
     if (x == 0x9e3779b9u) atomicXor(sink, x);  // practically never taken; keeps the chain alive
 }
 
-// four independent accumulator chains per wavefront, `iters` rounds of four MFMAs each
+// four independent accumulator chains per wavefront, `iters` rounds of four MFMAs each.  Operands are
+// pseudo-random finite values, different for every chain and lane: with constant or tiny operands the
+// data paths barely toggle, the chip draws less power, clocks higher and reports a rate that real
+// data never sees.
 __global__ __launch_bounds__(512) void mfma_bf16_kernel(int iters, float *sink)
 {
-    bf16x8 a, b;
-    for (int e = 0; e < 8; ++e) {
-        a[e] = (__bf16)(float)((threadIdx.x + e) & 3);
-        b[e] = (__bf16)0.5f;
-    }
+    typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
+    auto operand = [](uint32_t seed) {
+        u32x4v r;
+        for (int e = 0; e < 4; ++e) {
+            uint32_t h = (seed + 0x9e3779b9u * (e + 1)) * 2654435761u;
+            h ^= h >> 15;
+            h *= 2246822519u;
+            h ^= h >> 13;
+            // two bf16 per word: random sign and mantissa, exponent in [124, 127] (|x| in [0.125, 2))
+            r[e] = (h & 0x807f807fu) | 0x3e003e00u | ((h >> 3) & 0x01800180u);
+        }
+        return __builtin_bit_cast(bf16x8, r);
+    };
+    const uint32_t t = threadIdx.x + 977u * blockIdx.x;
+    const bf16x8 a0 = operand(8 * t), a1 = operand(8 * t + 1), a2 = operand(8 * t + 2), a3 = operand(8 * t + 3);
+    const bf16x8 b0 = operand(8 * t + 4), b1 = operand(8 * t + 5), b2 = operand(8 * t + 6), b3 = operand(8 * t + 7);
     f32x16 c0 = {}, c1 = {}, c2 = {}, c3 = {};
     for (int i = 0; i < iters; ++i) {
-        c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
-        c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c1, 0, 0, 0);
-        c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c2, 0, 0, 0);
-        c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c3, 0, 0, 0);
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, c1, 0, 0, 0);
+        c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, b2, c2, 0, 0, 0);
+        c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a3, b3, c3, 0, 0, 0);
     }
     const float x = c0[0] + c1[1] + c2[2] + c3[3];
-    if (x == -1.f) sink[0] = x;  // never true (all products are non-negative)
+    if (x == 12345.678f) sink[0] = x;  // practically never true; keeps the chains alive
 }
 
 }  // namespace
