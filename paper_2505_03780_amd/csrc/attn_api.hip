@@ -46,6 +46,8 @@ std::unordered_map<std::string, int> g_winner[2];  // [is_decode]: bucket key ->
 std::unordered_map<std::string, std::string> g_named;  // other kernel kinds: bucket key -> instance name
 std::atomic<int> g_forced[2] = {{-1}, {-1}};
 bool g_env_cache_tried = false;
+// bumped whenever the winner table may have changed (tune, load, clear): invalidates the per-thread memo
+std::atomic<uint64_t> g_generation{1};
 
 const Instance *all_decode_instances(int *count);
 const Instance *instances(int is_decode, int *n) { return is_decode ? all_decode_instances(n) : prefill_instances(n); }
@@ -361,6 +363,7 @@ int load_cache_locked(const char *path)
         if (id < 0) continue;
         g_winner[is_decode][cl.key] = id;
     }
+    g_generation.fetch_add(1, std::memory_order_release);
     return ATTN_OK;
 }
 
@@ -373,12 +376,28 @@ void maybe_load_env_cache()
     if (path && *path) (void)load_cache_locked(path);
 }
 
-int select_instance(const KParams &p, int dtype, int is_decode)
+// Everything the choice depends on.  A serving loop calls with the same shape over and over: the
+// last answer per thread and call kind is kept, so a hot call pays one comparison of this key
+// instead of building the bucket string, taking the lock and walking the instance table.
+struct SelectKey {
+    int32_t dtype, head_dim, num_q_heads, num_kv_heads, paged, block_size, causal, num_seqs, max_q_len, max_kv_len;
+    bool operator==(const SelectKey &o) const
+    {
+        return dtype == o.dtype && head_dim == o.head_dim && num_q_heads == o.num_q_heads && num_kv_heads == o.num_kv_heads &&
+               paged == o.paged && block_size == o.block_size && causal == o.causal && num_seqs == o.num_seqs &&
+               max_q_len == o.max_q_len && max_kv_len == o.max_kv_len;
+    }
+};
+struct SelectMemo {
+    uint64_t generation = 0;
+    SelectKey key{};
+    int id = -1;
+};
+
+int select_instance_slow(const KParams &p, int dtype, int is_decode)
 {
     int n;
     const Instance *t = instances(is_decode, &n);
-    const int forced = g_forced[is_decode].load();
-    if (forced >= 0) return forced < n && t[forced].valid(p) ? forced : ATTN_ERR_UNSUPPORTED;
     maybe_load_env_cache();
     {
         std::lock_guard<std::mutex> lk(g_mu);
@@ -387,6 +406,30 @@ int select_instance(const KParams &p, int dtype, int is_decode)
     }
     const int id = heuristic(p, is_decode);
     return id >= 0 ? id : ATTN_ERR_UNSUPPORTED;
+}
+
+int select_instance(const KParams &p, int dtype, int is_decode)
+{
+    const int forced = g_forced[is_decode].load();
+    if (forced >= 0) {
+        int n;
+        const Instance *t = instances(is_decode, &n);
+        return forced < n && t[forced].valid(p) ? forced : ATTN_ERR_UNSUPPORTED;
+    }
+    static thread_local SelectMemo memo[2];
+    SelectMemo &m = memo[is_decode];
+    const SelectKey key{dtype, p.head_dim, p.num_q_heads, p.num_kv_heads, p.block_table ? 1 : 0, p.block_size, p.causal,
+                        p.num_seqs, p.max_q_len, p.max_kv_len};
+    const uint64_t gen = g_generation.load(std::memory_order_acquire);
+    if (m.generation == gen && m.key == key) return m.id;
+    const int id = select_instance_slow(p, dtype, is_decode);
+    // the generation is read again: a table change that raced with the slow path must not be memoised
+    if (g_generation.load(std::memory_order_acquire) == gen) {
+        m.generation = gen;
+        m.key = key;
+        m.id = id;
+    }
+    return id;
 }
 
 size_t balanced_workspace_bytes(int num_seqs, int num_q_heads, int head_dim, int wgs)
@@ -735,6 +778,7 @@ int tune(const attn_args *shape, int is_decode, const char *cache_path, int iter
     {
         std::lock_guard<std::mutex> lk(g_mu);
         g_winner[is_decode][key] = best;
+        g_generation.fetch_add(1, std::memory_order_release);
     }
     if (flags & 1) fprintf(stderr, "[attn_tune] winner %s -> %s (%.2f us)\n", key.c_str(), t[best].name, best_us);
     if (!cache_path) return ATTN_OK;
@@ -868,6 +912,7 @@ void attn_clear_cache(void)
     g_winner[0].clear();
     g_winner[1].clear();
     g_named.clear();
+    g_generation.fetch_add(1, std::memory_order_release);
 }
 
 int attn_num_instances(int is_decode)

@@ -253,3 +253,25 @@ def test_kv_cache_write_validation_on_the_host():
     assert lib.attn_kv_cache_write(bad, None) == -2
     bad = A.KvWriteArgs.from_buffer_copy(a); bad.num_tokens = 0; bad.k_new = None
     assert lib.attn_kv_cache_write(bad, None) == 0
+
+
+def test_selection_memo_follows_cache_changes(tmp_path):
+    """The per-thread memo of the last selection must not outlive a change of the winner table."""
+    names_p = [A.attn_instance_name(False, i) for i in range(A.attn_num_instances(False))]
+    A.attn_clear_cache()
+    default = A.attn_selected_instance(_args(), False)
+    assert A.attn_selected_instance(_args(), False) == default  # memoised answer
+    other = next(i for i, n in enumerate(names_p) if "bf16_ring" in n and "hpw1" in n and i != default)
+    f = tmp_path / "c.txt"
+    f.write_text("attn-tune-cache-v1\n%s\tprefill|bf16|d128|hq32|hkv8|contig|bs0|c1|B2|q7|kv7\t%s\t1.0\n" % (A.attn_environment_key(), names_p[other]))
+    assert A.attn_load_cache(str(f)) == 0
+    assert A.attn_selected_instance(_args(), False) == other
+    A.attn_clear_cache()
+    assert A.attn_selected_instance(_args(), False) == default
+    A.attn_force_instance(False, other)
+    assert A.attn_selected_instance(_args(), False) == other
+    A.attn_force_instance(False, -1)
+    assert A.attn_selected_instance(_args(), False) == default
+    # a different shape is not answered from the memo of the previous one
+    assert "w8" in names_p[A.attn_selected_instance(_args(max_kv_len=8192, max_q_len=8192), False)]
+    assert A.attn_selected_instance(_args(), False) == default
