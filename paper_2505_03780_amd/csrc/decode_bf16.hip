@@ -11,11 +11,13 @@
 //  * All G query heads of the KV head ride in the 16 columns of
 //    v_mfma_f32_16x16x32_bf16 (S^T = K Q^T), so every K/V byte is fetched once
 //    for the whole group.
-//  * K rows go from HBM straight into MFMA A-operand registers (64 contiguous
-//    bytes per row and instruction, whole 256-byte rows per chunk); V rows are
-//    fetched with fully coalesced 128-bit loads, parked in a wave-private LDS
-//    tile and read back transposed (ds_read_b64_tr_b16).  The next chunk's loads
-//    are issued before the current chunk is consumed.
+//  * K and V rows are fetched as whole head slices (four rows x 256 contiguous
+//    bytes per wave-wide 128-bit load at D = 128) with the non-temporal hint:
+//    every byte is read once, and a load that covers only half of a 128-byte
+//    line (as MFMA operand order would) pays for the line twice under that hint.
+//    A wave-private LDS tile turns K into A-operand order (plain 128-bit reads)
+//    and then V into key-contiguous operands (ds_read_b64_tr_b16).  The next
+//    chunk's loads are issued before the current chunk is consumed.
 //  * Each part leaves an fp32 (partial output, max, sum) triple per query head;
 //    a second kernel merges the parts, one wavefront per (sequence, head).
 #include "kernel_params.hpp"
@@ -46,6 +48,13 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// K and V are read exactly once per call: the loads carry the non-temporal hint so that the stream
+// does not displace the caches' contents (measured on a 2 GiB read: 7.1 TB/s with the hint, 6.2 without)
+__device__ __forceinline__ u32x4 kv_load(const void *src)
+{
+    return __builtin_nontemporal_load((const u32x4 *)src);
+}
+
 constexpr int kChunk = 32;  // keys per wavefront step
 
 template <int HD, int WAVES>
@@ -53,6 +62,7 @@ struct DecodeCfg {
     static constexpr int kThreads = WAVES * 64;
     static constexpr int kVPitch = HD * 2 + 64;             // bytes per staged V row
     static constexpr int kVBytes = kChunk * kVPitch;        // per wave
+    static constexpr int kKPitch = HD * 2 + 16;             // bytes per staged K row (same tile, before V)
     static constexpr int kRedStride = HD + 2;               // floats per (wave, head) in the final reduction
     static constexpr int kRedBytes = WAVES * 16 * kRedStride * 4;
     static constexpr int kLdsBytes = WAVES * kVBytes > kRedBytes ? WAVES * kVBytes : kRedBytes;
@@ -119,15 +129,18 @@ __global__ __launch_bounds__(WAVES * 64) void decode_bf16_kernel(const KParams p
         const int64_t g0 = group_offset(c0), g1 = group_offset(c0 + 16);
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            const elem_t *kr = kbase + (t ? g1 : g0) + (int64_t)l16 * p.kv_stride_tok + 8 * lg;
+            // whole head slices (four rows x 256 bytes per wave-wide load at D = 128), like V
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) kreg[t][ks] = *(const u32x4 *)(kr + 32 * ks);
+            for (int i = 0; i < KS; ++i) {
+                const int row = lane / (HD / 8) + VROWS * i;  // 0..15
+                kreg[t][i] = kv_load(kbase + (t ? g1 : g0) + (int64_t)row * p.kv_stride_tok + 8 * (lane % (HD / 8)));
+            }
         }
 #pragma unroll
         for (int i = 0; i < VLD; ++i) {
             const int row = lane / (HD / 8) + VROWS * i;  // 0..31
             const elem_t *vr = vbase + (row < 16 ? g0 : g1) + (int64_t)(row & 15) * p.kv_stride_tok + 8 * (lane % (HD / 8));
-            vreg[i] = *(const u32x4 *)vr;
+            vreg[i] = kv_load(vr);
         }
     };
 
@@ -142,14 +155,25 @@ __global__ __launch_bounds__(WAVES * 64) void decode_bf16_kernel(const KParams p
     int c0 = k_lo + wave * kChunk;
     if (c0 < k_hi) load_chunk(c0);
     for (; c0 < k_hi; c0 += WAVES * kChunk) {
-        // consume the registers of this chunk: K feeds the MFMA directly, V is parked in LDS
+        // consume the registers of this chunk: K, then V, pass through the wave's LDS tile
         f32x4 sacc[2];
+        // the wave's LDS tile turns the K rows into MFMA operand order; V takes the tile over below
+        // (LDS instructions of one wave execute in order, so no wait is needed between the two uses)
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int i = 0; i < KS; ++i) {
+                const int row = 16 * t + lane / (HD / 8) + VROWS * i;
+                *(u32x4 *)(vst + row * C::kKPitch + 16 * (lane % (HD / 8))) = kreg[t][i];
+            }
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             sacc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                sacc[t] = DECODE_MFMA(__builtin_bit_cast(ex8, kreg[t][ks]), qf[ks], sacc[t], 0, 0, 0);
+            for (int ks = 0; ks < KS; ++ks) {
+                const ex8 kf = *(const ex8 *)(vst + (16 * t + l16) * C::kKPitch + 16 * lg + 64 * ks);
+                sacc[t] = DECODE_MFMA(kf, qf[ks], sacc[t], 0, 0, 0);
+            }
         }
         const bool tail = c0 + kChunk > k_hi;
 #pragma unroll
@@ -312,8 +336,7 @@ __device__ __forceinline__ void decode_stream_part(const KParams &p, unsigned ch
         const int blk = bt_row[key >> p.block_shift];
         return (int64_t)blk * p.kv_stride_block * 2 + (int64_t)(key & (p.block_size - 1)) * tok_bytes;
     };
-    // per-lane byte offsets inside a group: K in MFMA A-operand order, V fully coalesced
-    const uint32_t k_lane = (uint32_t)l16 * tok_bytes + 16 * lg;
+    // per-lane byte offsets inside a group, the same for K and V: whole head slices, fully coalesced
     uint32_t v_lane[VLD];
 #pragma unroll
     for (int i = 0; i < VLD; ++i) {
@@ -328,14 +351,13 @@ __device__ __forceinline__ void decode_stream_part(const KParams &p, unsigned ch
     auto load = [&](Regs &r, int64_t g0, int64_t g1) {
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            const unsigned char *kr = kbase + (t ? g1 : g0) + k_lane;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) r.k[t][ks] = *(const u32x4 *)(kr + 64 * ks);
+            for (int i = 0; i < KS; ++i) r.k[t][i] = kv_load(kbase + (t ? g1 : g0) + v_lane[i]);
         }
 #pragma unroll
         for (int i = 0; i < VLD; ++i) {
             const int row = lane / (HD / 8) + VROWS * i;
-            r.v[i] = *(const u32x4 *)(vbase + (row < 16 ? g0 : g1) + v_lane[i]);
+            r.v[i] = kv_load(vbase + (row < 16 ? g0 : g1) + v_lane[i]);
         }
     };
 
@@ -346,15 +368,28 @@ __device__ __forceinline__ void decode_stream_part(const KParams &p, unsigned ch
     const int v_rd = (4 * lg + (l16 >> 2)) * C::kVPitch + 8 * (l16 & 3);
 
     f32x4 sacc[2];
-    // consume: the chunk leaves its registers (K into the score MFMAs, V into the wave's LDS tile), so
+    // consume: the chunk leaves its registers (K through the wave's LDS tile into the score MFMAs, V into
+    // the tile), so
     // the same registers can take the loads of the chunk after next right away
     auto consume = [&](Regs &r, int c0) {
+        // K rows arrive as whole head slices (V's wave-wide shape); the wave's LDS tile turns them into
+        // MFMA operand order.  The tile is shared with V: LDS instructions of a wave execute in order,
+        // so these writes follow the previous chunk's V reads and the V writes below follow the K reads.
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int i = 0; i < KS; ++i) {
+                const int row = 16 * t + lane / (HD / 8) + VROWS * i;
+                *(u32x4 *)(vst + row * C::kKPitch + 16 * (lane % (HD / 8))) = r.k[t][i];
+            }
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             sacc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                sacc[t] = DECODE_MFMA(__builtin_bit_cast(ex8, r.k[t][ks]), qf[ks], sacc[t], 0, 0, 0);
+            for (int ks = 0; ks < KS; ++ks) {
+                const ex8 kf = *(const ex8 *)(vst + (16 * t + l16) * C::kKPitch + 16 * lg + 64 * ks);
+                sacc[t] = DECODE_MFMA(kf, qf[ks], sacc[t], 0, 0, 0);
+            }
         }
         const bool tail = c0 + kChunk > k_hi;
 #pragma unroll

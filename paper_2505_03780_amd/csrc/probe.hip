@@ -14,15 +14,25 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-// every lane reads 16 bytes per step, the grid strides over the buffer; the xor of everything read
-// goes out so that the loads cannot be dropped
+// every workgroup reads one contiguous piece of the buffer, 16 bytes per lane and step, eight steps
+// in flight, with the non-temporal hint (the access shape that measured fastest on this chip: 7.1 TB/s
+// against 6.2 without the hint and 5.3-6.2 for a grid-strided walk); the xor of everything read goes
+// out so that the loads cannot be dropped
 __global__ __launch_bounds__(256) void hbm_read_kernel(const u32x4 *src, size_t n_vec, uint32_t *sink)
 {
     u32x4 acc = {0u, 0u, 0u, 0u};
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
-#pragma unroll 8
-    for (; i < n_vec; i += stride) acc ^= src[i];  // eight loads in flight per lane
+    const size_t per = (n_vec + gridDim.x - 1) / gridDim.x;
+    const size_t lo = blockIdx.x * per;
+    const size_t hi = lo + per < n_vec ? lo + per : n_vec;
+    size_t i = lo + threadIdx.x;
+    for (; i + 7 * 256 < hi; i += 8 * 256) {
+        u32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(src + i + u * 256);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= v[u];
+    }
+    for (; i < hi; i += 256) acc ^= __builtin_nontemporal_load(src + i);
     const uint32_t x = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
     if (x == 0x9e3779b9u) atomicXor(sink, x);  // practically never taken; keeps the chain alive
 }
@@ -73,7 +83,7 @@ extern "C" int attn_probe_hbm_read(const void *buf, size_t bytes, void *sink4, v
     hipDeviceProp_t prop;
     if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) cus = prop.multiProcessorCount;
     (void)hipGetLastError();
-    hipLaunchKernelGGL(hbm_read_kernel, dim3((unsigned)(cus * 8)), dim3(256), 0, (hipStream_t)hip_stream, (const u32x4 *)buf, n_vec, (uint32_t *)sink4);
+    hipLaunchKernelGGL(hbm_read_kernel, dim3((unsigned)(cus * 4)), dim3(256), 0, (hipStream_t)hip_stream, (const u32x4 *)buf, n_vec, (uint32_t *)sink4);
     return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_ERR_HIP;
 }
 
