@@ -57,7 +57,7 @@ typedef enum attn_status {
 typedef enum attn_dtype {
     ATTN_F32 = 0, /* q, k, v, out are IEEE fp32; arithmetic is fp32 FMA */
     ATTN_BF16 = 1, /* q, k, v, out are bfloat16; products on bf16 MFMA, fp32 accumulation and softmax */
-    ATTN_F16 = 2   /* q, k, v, out are IEEE fp16; products on fp16 MFMA, fp32 accumulation and softmax; D = 128 */
+    ATTN_F16 = 2   /* q, k, v, out are IEEE fp16; products on fp16 MFMA, fp32 accumulation and softmax */
 } attn_dtype;
 
 typedef struct attn_args {
@@ -105,7 +105,7 @@ typedef struct attn_args {
  * builds on (same section; Fig. 2 "causal flash attention"): the score matrix
  * is never materialised.  Sequences with n_q = 0 write nothing.  A query with
  * no visible key (possible only when causal == 0 and seq_len == 0) gets zeros.
- * dtype ATTN_BF16 (D = 128 or 64), ATTN_F16 (D = 128) or ATTN_F32 (D = 64 or 128).
+ * dtype ATTN_BF16 (D = 128 or 64), ATTN_F16 (D = 128 or 64) or ATTN_F32 (D = 64 or 128).
  * Returns ATTN_OK after enqueueing, or a negative attn_status.
  */
 int attn_prefill_varlen(const attn_args *args, void *hip_stream);

@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libattn_gfx950.so")
-SOURCES = ["attn_api.hip", "prefill_f32.hip", "prefill_bf16.hip", "prefill_bf16_ring.hip", "prefill_f16_ring.hip", "decode_bf16.hip", "decode_f16.hip", "rmsnorm.hip", "kv_write.hip", "probe.hip"]
+SOURCES = ["attn_api.hip", "prefill_f32.hip", "prefill_bf16.hip", "prefill_bf16_ring.hip", "prefill_f16_ring.hip", "prefill_f16.hip", "decode_bf16.hip", "decode_f16.hip", "rmsnorm.hip", "kv_write.hip", "probe.hip"]
 # Packed fp32 instructions (v_pk_fma_f32 and friends) are switched off on purpose: some of their forms
 # have given wrong results on this hardware, and the kernels do not depend on them.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -864,6 +864,8 @@ const Instance *prefill_instances(int *count)
         v.insert(v.end(), t, t + n);
         t = prefill_ring_f16_instances(&n);
         v.insert(v.end(), t, t + n);
+        t = prefill_staged_f16_instances(&n);
+        v.insert(v.end(), t, t + n);
         return v;
     }();
     *count = (int)all.size();

@@ -65,6 +65,7 @@ const Instance *prefill_instances(int *count);         // all prefill instances,
 const Instance *prefill_ring_instances(int *count);    // LDS-ring, software-pipelined (D = 128), bf16
 const Instance *prefill_ring_f16_instances(int *count);  // the same kernel for fp16
 const Instance *prefill_staged_instances(int *count);  // register-staged double buffer (D = 64, 128)
+const Instance *prefill_staged_f16_instances(int *count);  // the same kernel for fp16
 const Instance *decode_instances(int *count);       // bf16
 const Instance *decode_f16_instances(int *count);   // fp16: the wave-per-head and token-balanced kernels
 

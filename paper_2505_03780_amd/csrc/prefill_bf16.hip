@@ -22,8 +22,22 @@
 namespace attn {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+// This file is compiled twice: as it stands for bf16, and included by prefill_f16.hip with
+// ATTN_PREFILL_ELEM_F16 defined for fp16 (the element type only changes the MFMA opcode and the
+// conversions of weights and outputs; a smaller set of instances is built).
+#ifdef ATTN_PREFILL_ELEM_F16
+typedef _Float16 elem_t;
+#define PREFILL_MFMA __builtin_amdgcn_mfma_f32_32x32x16_f16
+#define PREFILL_NAME "prefill_f16"
+constexpr int kElemDtype = kDtypeF16;
+#else
+typedef __bf16 elem_t;
+#define PREFILL_MFMA __builtin_amdgcn_mfma_f32_32x32x16_bf16
+#define PREFILL_NAME "prefill_bf16"
+constexpr int kElemDtype = kDtypeBf16;
+#endif
+typedef elem_t ex8 __attribute__((ext_vector_type(8)));
+typedef elem_t ex4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
@@ -90,15 +104,15 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_bf16_kernel(const KParams 
     const int t0w = t0 + (wave / HPW) * C::kWaveTok;
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane holds query column l32, 8 channels ----
-    const __bf16 *qbase = (const __bf16 *)p.q;
-    bf16x8 qf[QB][KSTEPS];
+    const elem_t *qbase = (const elem_t *)p.q;
+    ex8 qf[QB][KSTEPS];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         int t = t0w + qb * 32 + l32;
         t = t < n_q ? t : n_q - 1;
-        const __bf16 *src = qbase + (int64_t)(q0 + t) * p.q_stride_tok + (int64_t)head * p.q_stride_head + 8 * lhalf;
+        const elem_t *src = qbase + (int64_t)(q0 + t) * p.q_stride_tok + (int64_t)head * p.q_stride_head + 8 * lhalf;
 #pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) qf[qb][ks] = *(const bf16x8 *)(src + 16 * ks);
+        for (int ks = 0; ks < KSTEPS; ++ks) qf[qb][ks] = *(const ex8 *)(src + 16 * ks);
     }
 
     // ---- key range of this workgroup ---------------------------------------------------------
@@ -117,8 +131,8 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_bf16_kernel(const KParams 
     // ---- K/V tile loader: thread -> (row, 16-byte chunk) ------------------------------------
     const int ld_chunk = tid % C::kChunksPerRow;
     const int ld_row = tid / C::kChunksPerRow;
-    const __bf16 *kbase = (const __bf16 *)p.k;
-    const __bf16 *vbase = (const __bf16 *)p.v;
+    const elem_t *kbase = (const elem_t *)p.k;
+    const elem_t *vbase = (const elem_t *)p.v;
     const int kv0 = p.block_table ? 0 : p.kv_start_loc[s];
     const int32_t *bt_row = p.block_table ? p.block_table + (int64_t)s * p.block_table_stride : nullptr;
     auto row_offset = [&](int row) -> int64_t {
@@ -195,16 +209,16 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_bf16_kernel(const KParams 
             for (int kb = 0; kb < KB; ++kb) {
 #pragma unroll
                 for (int ks = 0; ks < KSTEPS; ++ks) {
-                    const bf16x8 kf = *(const bf16x8 *)(kt + kb * 32 * C::kKPitch + 32 * ks);
+                    const ex8 kf = *(const ex8 *)(kt + kb * 32 * C::kKPitch + 32 * ks);
 #pragma unroll
                     for (int qb = 0; qb < QB; ++qb)
-                        sacc[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], sacc[qb][kb], 0, 0, 0);
+                        sacc[qb][kb] = PREFILL_MFMA(kf, qf[qb][ks], sacc[qb][kb], 0, 0, 0);
                 }
             }
 
             // ---- mask + online softmax ---------------------------------------------------------
             const bool need_mask = (tile0 + BN - 1 > qpos_lo) || (tile0 + BN > n_kv);
-            bf16x8 pf[QB][KB][2];
+            ex8 pf[QB][KB][2];
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) {
                 float mloc = -INFINITY;
@@ -233,7 +247,7 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_bf16_kernel(const KParams 
                     for (int v = 0; v < 16; ++v) {
                         const float e = fast_exp2(sacc[qb][kb][v] - m_use);
                         rowsum += e;
-                        pf[qb][kb][v >> 3][v & 7] = (__bf16)e;
+                        pf[qb][kb][v >> 3][v & 7] = (elem_t)e;
                     }
                 }
                 l_run[qb] = l_run[qb] * alpha + rowsum;
@@ -255,10 +269,10 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_bf16_kernel(const KParams 
                         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)a);
                         const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a + 8 * C::kVPitch));
                         const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                        const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
+                        const ex8 vf = __builtin_bit_cast(ex8, both);
 #pragma unroll
                         for (int qb = 0; qb < QB; ++qb)
-                            oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][kb][ks], oacc[qb][db], 0, 0, 0);
+                            oacc[qb][db] = PREFILL_MFMA(vf, pf[qb][kb][ks], oacc[qb][db], 0, 0, 0);
                     }
                 }
             }
@@ -269,22 +283,22 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_bf16_kernel(const KParams 
     }
 
     // ---- epilogue: O / l -> bf16 -------------------------------------------------------------
-    __bf16 *obase = (__bf16 *)p.out;
+    elem_t *obase = (elem_t *)p.out;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         const float l = l_run[qb] + __shfl_xor(l_run[qb], 32);
         const float inv = l > 0.f ? 1.f / l : 0.f;
         const int t = t0w + qb * 32 + l32;
         if (t < n_q) {
-            __bf16 *dst = obase + (int64_t)(q0 + t) * p.o_stride_tok + (int64_t)head * p.o_stride_head + 4 * lhalf;
+            elem_t *dst = obase + (int64_t)(q0 + t) * p.o_stride_tok + (int64_t)head * p.o_stride_head + 4 * lhalf;
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
 #pragma unroll
                 for (int vq = 0; vq < 4; ++vq) {
-                    bf16x4 o;
+                    ex4 o;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = (__bf16)(oacc[qb][db][4 * vq + e] * inv);
-                    *(bf16x4 *)(dst + db * 32 + 8 * vq) = o;
+                    for (int e = 0; e < 4; ++e) o[e] = (elem_t)(oacc[qb][db][4 * vq + e] * inv);
+                    *(ex4 *)(dst + db * 32 + 8 * vq) = o;
                 }
             }
         }
@@ -294,7 +308,7 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_bf16_kernel(const KParams 
 template <int HD, int BN, int QB, int WAVES, int HPW>
 bool prefill_valid(const KParams &p)
 {
-    return p.dtype == kDtypeBf16 && p.head_dim == HD && p.group % HPW == 0;
+    return p.dtype == kElemDtype && p.head_dim == HD && p.group % HPW == 0;
 }
 
 template <int HD, int BN, int QB, int WAVES, int HPW>
@@ -315,12 +329,24 @@ hipError_t prefill_launch(const KParams &p, hipStream_t stream)
 
 #define PREFILL_INSTANCE(HD, BN, QB, WAVES, HPW)                                                              \
     {                                                                                                         \
-        "prefill_bf16 d" #HD " bn" #BN " qb" #QB " w" #WAVES " hpw" #HPW, (WAVES / HPW) * 32 * QB * HPW, BN,  \
+        PREFILL_NAME " d" #HD " bn" #BN " qb" #QB " w" #WAVES " hpw" #HPW, (WAVES / HPW) * 32 * QB * HPW, BN,  \
             WAVES, HPW, 2, 0, prefill_valid<HD, BN, QB, WAVES, HPW>, prefill_launch<HD, BN, QB, WAVES, HPW>     \
     }
 
 }  // namespace
 
+#ifdef ATTN_PREFILL_ELEM_F16
+const Instance *prefill_staged_f16_instances(int *count)
+{
+    static const Instance table[] = {
+        PREFILL_INSTANCE(128, 64, 1, 4, 4), PREFILL_INSTANCE(128, 64, 1, 4, 1), PREFILL_INSTANCE(128, 64, 1, 8, 8),
+        PREFILL_INSTANCE(64, 64, 2, 4, 4),  PREFILL_INSTANCE(64, 64, 2, 4, 2),  PREFILL_INSTANCE(64, 64, 2, 4, 1),
+        PREFILL_INSTANCE(64, 128, 2, 4, 1),
+    };
+    *count = (int)(sizeof(table) / sizeof(table[0]));
+    return table;
+}
+#else
 const Instance *prefill_staged_instances(int *count)
 {
     // Built inside a host function so that the table of host function pointers is not
@@ -345,5 +371,7 @@ const Instance *prefill_staged_instances(int *count)
     *count = (int)(sizeof(table) / sizeof(table[0]));
     return table;
 }
+
+#endif
 
 }  // namespace attn

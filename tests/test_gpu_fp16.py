@@ -1,4 +1,4 @@
-"""GPU parity of the fp16 instances (prefill ring kernel, paged decode) against the fp64 oracle."""
+"""GPU parity of the fp16 instances (prefill ring and register-staged kernels, paged decode) against the fp64 oracle."""
 import numpy as np
 import pytest
 import torch
@@ -34,9 +34,9 @@ def _valid_instances(dw, is_decode):
     return ids
 
 
-@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (4, 4), (4, 2), (32, 8)])
-def test_prefill_contiguous_ragged_every_f16_instance(Hq, Hkv):
-    wl = W.as_f16(W.make_prefill_contiguous(121, RAGGED, Hq, Hkv, 128))
+@pytest.mark.parametrize("Hq,Hkv,D", [(8, 2, 128), (4, 4, 128), (4, 2, 128), (32, 8, 128), (8, 2, 64), (4, 4, 64)])
+def test_prefill_contiguous_ragged_every_f16_instance(Hq, Hkv, D):
+    wl = W.as_f16(W.make_prefill_contiguous(121, RAGGED, Hq, Hkv, D))
     dw = DeviceWorkload(wl)
     assert dw.q.dtype == torch.float16
     ref = oracle.attention(oracle_problem(wl))
@@ -82,12 +82,15 @@ def test_full_size_configs_in_f16_and_what_is_refused():
     check_full(W.as_f16(W.config2()))
     print("config 3 in fp16 (sampled)", flush=True)
     check_sampled(W.as_f16(W.config3()), 400, seed=33)
-    # head size 64 has no fp16 prefill instance: refused, nothing silently converted
-    small = W.as_f16(W.make_prefill_contiguous(125, [64, 64], 8, 2, 64))
+    # a head size without instances is refused, nothing silently converted
+    small = W.as_f16(W.make_prefill_contiguous(125, [64, 64], 8, 2, 32))
     dw = DeviceWorkload(small)
     with pytest.raises(A.AttnError) as e:
         dw.run(False)
-    assert e.value.status == -4
+    assert e.value.status in (-2, -4)
+    # head size 64 over a paged prefix in fp16 (register-staged kernel)
+    paged64 = W.as_f16(W.make_paged(127, "prefill", [64, 1, 130], [64, 300, 130 + 256], 8, 2, 64, 16, 100))
+    check_full(paged64, what="fp16 d64 chunked prefill")
     # the autotuner works on fp16 buckets too
     wl = W.as_f16(W.make_prefill_contiguous(126, [300, 200], 32, 8, 128))
     dw = DeviceWorkload(wl)

@@ -36,7 +36,7 @@ def test_random_shape(seed):
     kind = ["prefill", "chunked", "decode"][seed % 3]
     Hq, Hkv = HEADS[int(rng.integers(len(HEADS)))]
     f16 = bool(rng.integers(2))
-    D = 128 if (f16 and kind != "decode") else int(rng.choice([64, 128]))
+    D = int(rng.choice([64, 128]))
     B = int(rng.integers(1, 9))
     causal = True
     if kind == "prefill":
