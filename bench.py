@@ -39,7 +39,7 @@ MEASURED_TRAFFIC_BYTES = {
     ("c5_decode_70b_long", "decode_bf16_balanced"): (2 * (757307 + 4479) + 8700 + 256) * 1024,
     ("c3_prefill_8b", "prefill_bf16_ring"): (2 * 93007 + 70104) * 1024,
     ("c4_chunked_prefill", "prefill_bf16_ring seqmajor"): (2 * 213334 + 65536) * 1024,
-    ("rmsnorm_8b_t8192_h4096", "rmsnorm_bf16"): (2 * 65591 + 131072) * 1024,
+    ("rmsnorm_8b_t8192_h4096", "rmsnorm"): (2 * 65591 + 131072) * 1024,
 }
 
 

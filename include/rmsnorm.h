@@ -10,8 +10,8 @@
  *     out[t, i]   = z[t, i] / sqrt(mean_i z[t, i]^2 + eps) * weight[i]
  *     residual[t] = z[t]                                 (written back in place)
  *
- * The sum z, its mean square and the product are taken in fp32 from the bf16 inputs; out and the new
- * residual are rounded to bf16 (nearest even) once.  One pass over HBM: every row is read once and
+ * The sum z, its mean square and the product are taken in fp32 from the bf16 (or fp16) inputs; out
+ * and the new residual are rounded to the element type (nearest even) once.  One pass over HBM: every row is read once and
  * written once, held in registers in between.
  *
  * Conventions are those of attn.h: every pointer in rmsnorm_args is a DEVICE pointer owned by the
@@ -33,7 +33,7 @@ extern "C" {
 
 typedef struct rmsnorm_args {
     uint32_t struct_bytes; /* = sizeof(rmsnorm_args) */
-    int32_t dtype;         /* ATTN_BF16 (1); other types are rejected with ATTN_ERR_DTYPE */
+    int32_t dtype;         /* ATTN_BF16 (1) or ATTN_F16 (2) for x, residual, weight and out; else ATTN_ERR_DTYPE */
     int32_t num_tokens;    /* T rows; 0 is allowed (nothing happens) */
     int32_t hidden;        /* H, a multiple of 8, at most 16384 */
     const void *x;         /* [T, H] */

@@ -39,13 +39,34 @@ struct RmsParams {
     int64_t x_stride, residual_stride, out_stride;
     int32_t num_tokens, hidden;
     float eps, inv_hidden;
+    int32_t f16;  // element type: 0 = bf16, 1 = IEEE fp16
 };
 
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-// two fp32 -> packed bf16, round to nearest even (inputs are finite or inf; NaN payloads are kept quiet)
-__device__ __forceinline__ uint32_t pack_bf16(float a, float b)
+// two packed elements <-> fp32; the stores round to nearest even
+template <bool F16>
+__device__ __forceinline__ float elem_lo(uint32_t w)
 {
+    typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+    if (F16) return (float)__builtin_bit_cast(f16x2, w)[0];
+    return __uint_as_float(w << 16);
+}
+template <bool F16>
+__device__ __forceinline__ float elem_hi(uint32_t w)
+{
+    typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+    if (F16) return (float)__builtin_bit_cast(f16x2, w)[1];
+    return __uint_as_float(w & 0xffff0000u);
+}
+template <bool F16>
+__device__ __forceinline__ uint32_t pack_elems(float a, float b)
+{
+    if (F16) {
+        typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+        f16x2 v;
+        v[0] = (_Float16)a;
+        v[1] = (_Float16)b;
+        return __builtin_bit_cast(uint32_t, v);
+    }
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
     bf16x2 v;
     v[0] = (__bf16)a;
@@ -53,7 +74,7 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
     return __builtin_bit_cast(uint32_t, v);
 }
 
-template <int TPR, int VPT, int ROWS>
+template <bool F16, int TPR, int VPT, int ROWS>
 __global__ __launch_bounds__(TPR *ROWS) void rmsnorm_kernel(const RmsParams p)
 {
     constexpr int WAVES_PER_ROW = TPR > 64 ? TPR / 64 : 1;
@@ -81,8 +102,8 @@ __global__ __launch_bounds__(TPR *ROWS) void rmsnorm_kernel(const RmsParams p)
         }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            z[k][2 * e] = bf16_lo(a[e]) + bf16_lo(b[e]);
-            z[k][2 * e + 1] = bf16_hi(a[e]) + bf16_hi(b[e]);
+            z[k][2 * e] = elem_lo<F16>(a[e]) + elem_lo<F16>(b[e]);
+            z[k][2 * e + 1] = elem_hi<F16>(a[e]) + elem_hi<F16>(b[e]);
             ss = __builtin_fmaf(z[k][2 * e], z[k][2 * e], ss);
             ss = __builtin_fmaf(z[k][2 * e + 1], z[k][2 * e + 1], ss);
         }
@@ -95,7 +116,7 @@ __global__ __launch_bounds__(TPR *ROWS) void rmsnorm_kernel(const RmsParams p)
             if (i < nvec) {
                 u32x4 o;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) o[e] = pack_bf16(z[k][2 * e], z[k][2 * e + 1]);
+                for (int e = 0; e < 4; ++e) o[e] = pack_elems<F16>(z[k][2 * e], z[k][2 * e + 1]);
                 RMS_ST(o, (u32x4 *)(rr + 16 * i));
             }
         }
@@ -123,7 +144,7 @@ __global__ __launch_bounds__(TPR *ROWS) void rmsnorm_kernel(const RmsParams p)
             u32x4 o;
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-                o[e] = pack_bf16(z[k][2 * e] * inv * bf16_lo(w4[e]), z[k][2 * e + 1] * inv * bf16_hi(w4[e]));
+                o[e] = pack_elems<F16>(z[k][2 * e] * inv * elem_lo<F16>(w4[e]), z[k][2 * e + 1] * inv * elem_hi<F16>(w4[e]));
             RMS_ST(o, (u32x4 *)(orow + 16 * i));
         }
     }
@@ -140,13 +161,16 @@ hipError_t rms_launch(const RmsParams &p, hipStream_t stream)
 {
     const unsigned blocks = (unsigned)((p.num_tokens + ROWS - 1) / ROWS);
     if (blocks == 0) return hipSuccess;
-    hipLaunchKernelGGL((rmsnorm_kernel<TPR, VPT, ROWS>), dim3(blocks), dim3(TPR * ROWS), 0, stream, p);
+    if (p.f16)
+        hipLaunchKernelGGL((rmsnorm_kernel<true, TPR, VPT, ROWS>), dim3(blocks), dim3(TPR * ROWS), 0, stream, p);
+    else
+        hipLaunchKernelGGL((rmsnorm_kernel<false, TPR, VPT, ROWS>), dim3(blocks), dim3(TPR * ROWS), 0, stream, p);
     return hipGetLastError();
 }
 
 #define RMS_INSTANCE(TPR, VPT, ROWS)                                                                   \
     {                                                                                                  \
-        "rmsnorm_bf16 tpr" #TPR " vpt" #VPT " rows" #ROWS, TPR, VPT, ROWS, rms_launch<TPR, VPT, ROWS> \
+        "rmsnorm tpr" #TPR " vpt" #VPT " rows" #ROWS, TPR, VPT, ROWS, rms_launch<TPR, VPT, ROWS>      \
     }
 
 const RmsInstance kInstances[] = {
@@ -173,7 +197,7 @@ int validate(const rmsnorm_args *a)
 {
     if (!a) return ATTN_ERR_NULL;
     if (a->struct_bytes != sizeof(rmsnorm_args)) return ATTN_ERR_SHAPE;
-    if (a->dtype != ATTN_BF16) return ATTN_ERR_DTYPE;
+    if (a->dtype != ATTN_BF16 && a->dtype != ATTN_F16) return ATTN_ERR_DTYPE;
     if (a->num_tokens < 0 || a->hidden <= 0) return ATTN_ERR_SHAPE;
     if (a->hidden % 8 != 0 || a->hidden > 16384) return ATTN_ERR_UNSUPPORTED;
     if (a->num_tokens == 0) return ATTN_OK;
@@ -198,6 +222,7 @@ RmsParams to_params(const rmsnorm_args *a)
     p.hidden = a->hidden;
     p.eps = a->eps;
     p.inv_hidden = 1.0f / (float)a->hidden;
+    p.f16 = a->dtype == ATTN_F16;
     return p;
 }
 
@@ -211,7 +236,7 @@ int ilog2_ceil(int x)
 std::string bucket_key(const rmsnorm_args *a)
 {
     char buf[96];
-    snprintf(buf, sizeof buf, "rmsnorm|bf16|h%d|res%d|T%d", a->hidden, a->residual ? 1 : 0, ilog2_ceil(std::max(1, a->num_tokens)));
+    snprintf(buf, sizeof buf, "rmsnorm|%s|h%d|res%d|T%d", a->dtype == ATTN_F16 ? "f16" : "bf16", a->hidden, a->residual ? 1 : 0, ilog2_ceil(std::max(1, a->num_tokens)));
     return buf;
 }
 
@@ -257,7 +282,8 @@ int run(const rmsnorm_args *a, hipStream_t stream, int override_id)
     return kInstances[id].launch(to_params(a), stream) == hipSuccess ? ATTN_OK : ATTN_ERR_HIP;
 }
 
-__global__ void fill_bf16_kernel(uint16_t *dst, size_t n, uint32_t seed)
+// pseudo-random values in [-2, 2), truncated to bf16 or rounded to fp16
+__global__ void fill_elems_kernel(uint16_t *dst, size_t n, uint32_t seed, int f16)
 {
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
         uint32_t h = (uint32_t)i * 2654435761u ^ seed;
@@ -265,7 +291,8 @@ __global__ void fill_bf16_kernel(uint16_t *dst, size_t n, uint32_t seed)
         h *= 2246822519u;
         h ^= h >> 13;
         const float f = ((int)(h & 0xffff) - 32768) * (1.f / 16384.f);
-        dst[i] = (uint16_t)(__float_as_uint(f) >> 16);
+        const _Float16 hf = (_Float16)f;
+        dst[i] = f16 ? __builtin_bit_cast(uint16_t, hf) : (uint16_t)(__float_as_uint(f) >> 16);
     }
 }
 
@@ -273,7 +300,7 @@ int tune(const rmsnorm_args *shape, const char *cache_path, int iters, int flags
 {
     if (!shape) return ATTN_ERR_NULL;
     if (shape->struct_bytes != sizeof(rmsnorm_args)) return ATTN_ERR_SHAPE;
-    if (shape->dtype != ATTN_BF16) return ATTN_ERR_DTYPE;
+    if (shape->dtype != ATTN_BF16 && shape->dtype != ATTN_F16) return ATTN_ERR_DTYPE;
     if (shape->num_tokens <= 0 || shape->hidden <= 0) return ATTN_ERR_SHAPE;
     if (shape->hidden % 8 != 0 || shape->hidden > 16384) return ATTN_ERR_UNSUPPORTED;
     if (iters <= 0) iters = 20;
@@ -289,9 +316,10 @@ int tune(const rmsnorm_args *shape, const char *cache_path, int iters, int flags
             release();
             return ATTN_ERR_HIP;
         }
-    hipLaunchKernelGGL(fill_bf16_kernel, dim3(2048), dim3(256), 0, 0, (uint16_t *)bufs[0], n, 11u);
-    hipLaunchKernelGGL(fill_bf16_kernel, dim3(2048), dim3(256), 0, 0, (uint16_t *)bufs[1], n, 12u);
-    hipLaunchKernelGGL(fill_bf16_kernel, dim3(64), dim3(256), 0, 0, (uint16_t *)bufs[3], (size_t)shape->hidden, 13u);
+    const int f16 = shape->dtype == ATTN_F16;
+    hipLaunchKernelGGL(fill_elems_kernel, dim3(2048), dim3(256), 0, 0, (uint16_t *)bufs[0], n, 11u, f16);
+    hipLaunchKernelGGL(fill_elems_kernel, dim3(2048), dim3(256), 0, 0, (uint16_t *)bufs[1], n, 12u, f16);
+    hipLaunchKernelGGL(fill_elems_kernel, dim3(64), dim3(256), 0, 0, (uint16_t *)bufs[3], (size_t)shape->hidden, 13u, f16);
     rmsnorm_args a = *shape;
     a.x = bufs[0];
     a.residual = shape->residual ? bufs[1] : nullptr;

@@ -120,9 +120,36 @@ def test_in_place_output_zero_rows_large_values_and_errors():
     with pytest.raises(A.AttnError) as e:
         A.rmsnorm_fused_add(torch.zeros(2, 1001, dtype=torch.bfloat16, device="cuda"), w, torch.zeros(2, 1001, dtype=torch.bfloat16, device="cuda"), 1e-6)
     assert e.value.status == -4
-    with pytest.raises(A.AttnError) as e:  # only bf16 rows
-        A.rmsnorm_fused_add(torch.zeros(2, 1024, dtype=torch.float16, device="cuda"), w, o, 1e-6)
+    with pytest.raises(A.AttnError) as e:  # bf16 or fp16 rows only
+        A.rmsnorm_fused_add(torch.zeros(2, 1024, dtype=torch.float32, device="cuda"), w, o, 1e-6)
     assert e.value.status == -3
+
+
+@pytest.mark.parametrize("hidden", [64, 1000, 4096, 16384])
+def test_fp16_rows_every_instance(hidden):
+    """fp16 inputs, the same oracle; one rounding to fp16 (11 significant bits) instead of bf16."""
+    wl = W.make_rmsnorm(300 + hidden, 37, hidden, True)
+    # the bf16 workload's values rounded to fp16 (exact but for values below fp16's subnormal range), then
+    # widened exactly for the oracle
+    x64, r64, w64 = (W.bf16_bits_to_f32(b).astype(np.float16).astype(np.float64) for b in (wl.x, wl.residual, wl.weight))
+    h = lambda a: torch.from_numpy(a.astype(np.float16)).cuda()
+    y_ref, z_ref = oracle.rms_norm(x64, w64, wl.eps, r64)
+    ran = 0
+    for i in range(A.rmsnorm_num_instances()):
+        x, r, w = h(x64), h(r64), h(w64)
+        out = torch.full_like(x, float("nan"))
+        A.rmsnorm_force_instance(i)
+        if A.rmsnorm_selected_instance(A.make_rmsnorm_args(x, w, out, wl.eps, r)) != i:
+            continue
+        A.rmsnorm_fused_add(x, w, out, wl.eps, residual=r)
+        torch.cuda.synchronize()
+        for got, ref, what in ((_f64(out), y_ref, "out"), (_f64(r), z_ref, "residual")):
+            assert np.all(np.isfinite(got))
+            err = np.abs(got - ref)
+            bound = (2.0 ** -11 + 2.0 ** -20) * np.abs(ref) + 2.0 ** -25  # half an fp16 ulp; subnormal floor
+            assert np.all(err <= bound), "fp16 %s %s: %.3e of bound" % (what, A.rmsnorm_instance_name(i), float(np.max(err / bound)))
+        ran += 1
+    assert ran >= 1
 
 
 def test_tune_records_a_winner_in_the_shared_cache_file(tmp_path):

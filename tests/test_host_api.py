@@ -215,14 +215,14 @@ def test_rmsnorm_validation_and_selection_on_the_host():
     names = [A.rmsnorm_instance_name(i) for i in range(A.rmsnorm_num_instances())]
     assert len(set(names)) == len(names) >= 10
     # the row is spread over as many lanes as it has 16-byte vectors (one vector per lane), up to 1024
-    assert names[A.rmsnorm_selected_instance(_rms(num_tokens=8192))] == "rmsnorm_bf16 tpr512 vpt1 rows1"
-    assert names[A.rmsnorm_selected_instance(_rms(hidden=8192, x_stride=8192, out_stride=8192, residual_stride=8192))] == "rmsnorm_bf16 tpr1024 vpt1 rows1"
-    assert names[A.rmsnorm_selected_instance(_rms(hidden=1024))] == "rmsnorm_bf16 tpr256 vpt1 rows1"
-    assert names[A.rmsnorm_selected_instance(_rms(hidden=16384, x_stride=16384, out_stride=16384, residual_stride=16384))] == "rmsnorm_bf16 tpr1024 vpt2 rows1"
+    assert names[A.rmsnorm_selected_instance(_rms(num_tokens=8192))] == "rmsnorm tpr512 vpt1 rows1"
+    assert names[A.rmsnorm_selected_instance(_rms(hidden=8192, x_stride=8192, out_stride=8192, residual_stride=8192))] == "rmsnorm tpr1024 vpt1 rows1"
+    assert names[A.rmsnorm_selected_instance(_rms(hidden=1024))] == "rmsnorm tpr256 vpt1 rows1"
+    assert names[A.rmsnorm_selected_instance(_rms(hidden=16384, x_stride=16384, out_stride=16384, residual_stride=16384))] == "rmsnorm tpr1024 vpt2 rows1"
     # every supported hidden size has at least one instance; a forced one that does not fit is refused
     for h in range(8, 16385, 8):
         assert A.rmsnorm_selected_instance(_rms(hidden=h, x_stride=h, out_stride=h, residual_stride=h)) >= 0, h
-    A.rmsnorm_force_instance(names.index("rmsnorm_bf16 tpr64 vpt2 rows4"))
+    A.rmsnorm_force_instance(names.index("rmsnorm tpr64 vpt2 rows4"))
     assert A.rmsnorm_selected_instance(_rms()) == -4
     A.rmsnorm_force_instance(-1)
     assert lib.rmsnorm_tune(None, None, 1, 0) == -1
