@@ -32,6 +32,11 @@
  *    host and returns ATTN_ERR_SHAPE if they are inconsistent (a debugging mode:
  *    synchronous, not capturable).
  *  - Hot calls are re-entrant; the winner cache is guarded by a mutex.
+ *  - Environment, each read once per process: ATTN_TUNE_CACHE=<file> (winner cache loaded on the
+ *    first hot call), ATTN_FORCE_INSTANCE=<exact instance name> (that instance wherever it is valid
+ *    for the shape, the usual choice elsewhere), ATTN_LOG=1 (one line on stderr whenever the
+ *    instance for a new shape is resolved: kind, bucket key, instance, reason),
+ *    ATTN_DEBUG_VALIDATE=1 (above).
  */
 #ifndef ATTN_H_
 #define ATTN_H_

@@ -394,17 +394,56 @@ struct SelectMemo {
     int id = -1;
 };
 
+// ATTN_FORCE_INSTANCE=<exact instance name>: calls of the kind that has an instance of that name use
+// it whenever it is valid for the shape (and fall back to the usual choice when it is not), as if
+// it were every bucket's winner.  ATTN_LOG=1: one line on stderr whenever a shape is resolved.
+// Both are read once.
+struct EnvKnobs {
+    int forced[2] = {-1, -1};
+    bool log = false;
+};
+
+const EnvKnobs &env_knobs()
+{
+    static const EnvKnobs k = [] {
+        EnvKnobs e;
+        const char *lg = getenv("ATTN_LOG");
+        e.log = lg && lg[0] == '1';
+        if (const char *name = getenv("ATTN_FORCE_INSTANCE"))
+            for (int d = 0; d < 2; ++d) e.forced[d] = instance_by_name(d, name);
+        return e;
+    }();
+    return k;
+}
+
 int select_instance_slow(const KParams &p, int dtype, int is_decode)
 {
     int n;
     const Instance *t = instances(is_decode, &n);
     maybe_load_env_cache();
-    {
-        std::lock_guard<std::mutex> lk(g_mu);
-        auto it = g_winner[is_decode].find(bucket_key(p, dtype, is_decode));
-        if (it != g_winner[is_decode].end() && it->second < n && t[it->second].valid(p)) return it->second;
+    const EnvKnobs &env = env_knobs();
+    const std::string key = bucket_key(p, dtype, is_decode);
+    int id = -1;
+    const char *why = "heuristic";
+    if (env.forced[is_decode] >= 0 && t[env.forced[is_decode]].valid(p)) {
+        id = env.forced[is_decode];
+        why = "ATTN_FORCE_INSTANCE";
     }
-    const int id = heuristic(p, is_decode);
+    if (id < 0) {
+        std::lock_guard<std::mutex> lk(g_mu);
+        auto it = g_winner[is_decode].find(key);
+        if (it != g_winner[is_decode].end() && it->second < n && t[it->second].valid(p)) {
+            id = it->second;
+            why = "tuned";
+        }
+    }
+    if (id < 0) id = heuristic(p, is_decode);
+    if (env.log) {
+        if (id >= 0)
+            fprintf(stderr, "[attn] %s %s -> %s (%s)\n", is_decode ? "decode" : "prefill", key.c_str(), t[id].name, why);
+        else
+            fprintf(stderr, "[attn] %s %s -> no valid instance\n", is_decode ? "decode" : "prefill", key.c_str());
+    }
     return id >= 0 ? id : ATTN_ERR_UNSUPPORTED;
 }
 

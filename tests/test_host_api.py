@@ -275,3 +275,29 @@ def test_selection_memo_follows_cache_changes(tmp_path):
     # a different shape is not answered from the memo of the previous one
     assert "w8" in names_p[A.attn_selected_instance(_args(max_kv_len=8192, max_q_len=8192), False)]
     assert A.attn_selected_instance(_args(), False) == default
+
+
+def test_environment_knobs_force_and_log_in_a_fresh_process():
+    """ATTN_FORCE_INSTANCE and ATTN_LOG are read once per process, so they are checked in a child."""
+    import subprocess
+    import sys
+
+    code = (
+        "import sys; sys.path.insert(0, %r); sys.path.insert(0, %r)\n"
+        "import test_host_api as T, paper_2505_03780_amd as A\n"
+        "d = A.attn_selected_instance(T._paged(total_q=4, max_q_len=1, max_kv_len=4096), True)\n"
+        "p = A.attn_selected_instance(T._args(), False)\n"
+        "s = A.attn_selected_instance(T._paged(total_q=4, max_q_len=1, max_kv_len=4096, head_dim=64, q_stride_head=64, "
+        "o_stride_head=64, kv_stride_head=64), True)\n"
+        "print(A.attn_instance_name(True, d)); print(A.attn_instance_name(False, p)); print(A.attn_instance_name(True, s))\n"
+    ) % (ROOT, os.path.join(ROOT, "tests"))
+    env = dict(os.environ, ATTN_FORCE_INSTANCE="decode_bf16_seq d128 w8 split512", ATTN_LOG="1")
+    env.pop("ATTN_TUNE_CACHE", None)
+    r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stderr
+    out = r.stdout.strip().splitlines()
+    assert out[0] == "decode_bf16_seq d128 w8 split512"          # forced where valid
+    assert out[1].startswith("prefill_bf16_ring")                 # the other kind is untouched
+    assert out[2].startswith("decode_bf16") and "d64" in out[2]   # not valid for D = 64: the usual choice
+    log = [l for l in r.stderr.splitlines() if l.startswith("[attn] ")]
+    assert len(log) == 3 and "ATTN_FORCE_INSTANCE" in log[0] and "(heuristic)" in log[1] and "decode|" in log[0].replace(" ", "|")
