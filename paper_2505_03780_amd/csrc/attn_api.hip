@@ -254,7 +254,15 @@ int heuristic(const KParams &p, int is_decode)
             int sl = 256;
             while (sl * 2 <= want && sl < 4096) sl *= 2;
             if (sl >= p.max_kv_len) sl = 0;
-            id = find_instance(1, p, 4, 16, 32, 0, sl);
+            // the merge takes 32 parts per round trip: a long context in few units gets longer parts and
+            // eight waves per workgroup rather than more parts
+            bool wide = false;
+            while (sl > 0 && sl < 4096 && (p.max_kv_len + sl - 1) / sl > 32) {
+                sl *= 2;
+                wide = true;
+            }
+            if (wide) id = find_instance(1, p, 8, 16, 32, 0, sl);
+            if (id < 0) id = find_instance(1, p, 4, 16, 32, 0, sl);
             if (id < 0) id = find_instance(1, p, 4, 16, 32, 0, 0);
             if (id < 0) id = find_instance(1, p, 8, 16, 32, 0, sl);  // fp16 has the wave-per-head family only
             if (id < 0) id = find_instance(1, p, 8, 16, 32, 0, 0);

@@ -131,6 +131,11 @@ def test_instance_tables_and_heuristic_selection():
     # a small batch of short contexts: one KV head per workgroup, fixed parts
     small = _paged(num_seqs=4, total_q=4, max_q_len=1, max_kv_len=4096, block_table_stride=256)
     assert names_d[A.attn_selected_instance(small, True)].startswith("decode_bf16 d128 w4 split")
+    # one long context: parts long enough that the merge takes them in one round trip (32), eight waves
+    one_long = _paged(num_seqs=1, total_q=1, max_q_len=1, max_kv_len=16384, block_table_stride=1024)
+    assert names_d[A.attn_selected_instance(one_long, True)] == "decode_bf16 d128 w8 split512"
+    one_mid = _paged(num_seqs=1, total_q=1, max_q_len=1, max_kv_len=4096, block_table_stride=256)
+    assert names_d[A.attn_selected_instance(one_mid, True)] == "decode_bf16 d128 w4 split256"
     few_heads = _paged(num_seqs=512, total_q=512, max_q_len=1, max_kv_len=200, num_q_heads=4, num_kv_heads=1)
     assert "split0" in names_d[A.attn_selected_instance(few_heads, True)]
     # a forced instance that does not fit the shape is refused, not silently replaced
