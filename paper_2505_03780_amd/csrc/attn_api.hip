@@ -247,7 +247,12 @@ int heuristic(const KParams &p, int is_decode)
         // per workgroup and fixed parts: enough workgroups to fill the chip several times over, parts
         // no shorter than 256 keys.
         const int64_t key_bound = (int64_t)p.num_seqs * p.max_kv_len;
-        if (p.num_kv_heads >= 4 && key_bound >= 100000) id = find_instance(1, p, 8, 16, 32, 0, -1);
+        if (p.num_kv_heads >= 4 && key_bound >= 100000) {
+            // two workgroups of four heads per compute unit measured 0.5-2 % ahead of one of eight from
+            // eight KV heads on, 1-2 % behind at four
+            if (p.num_kv_heads >= 8) id = find_instance(1, p, 4, 16, 32, 0, -1);
+            if (id < 0) id = find_instance(1, p, 8, 16, 32, 0, -1);
+        }
         if (id < 0) {
             const int64_t units = (int64_t)p.num_seqs * p.num_kv_heads;
             int64_t want = units * (int64_t)p.max_kv_len / 2048;
