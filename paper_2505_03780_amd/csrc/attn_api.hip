@@ -232,7 +232,7 @@ int heuristic(const KParams &p, int is_decode)
         // Sequences of many query tiles, many sequences, or a cached prefix that dominates the key
         // range: run the tiles of a sequence side by side so that they share its K/V in one L2.
         const bool prefix = p.block_table && p.max_kv_len >= 2 * p.max_q_len;
-        const int order = (prefix || p.max_kv_len >= 2048 || p.num_seqs >= 32) ? 1 : 0;
+        const int order = (prefix || p.max_kv_len >= 4096 || p.num_seqs >= 32) ? 1 : 0;
         // Short sequences: two small workgroups per compute unit hide each other's prologue and
         // epilogue; long ones: one large workgroup with the deeper ring.
         const bool small_wg = p.max_kv_len <= 2048;

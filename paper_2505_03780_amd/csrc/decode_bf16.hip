@@ -82,8 +82,11 @@ __global__ __launch_bounds__(WAVES * 64) void decode_bf16_kernel(const KParams p
     int bid = blockIdx.x;
     const int kvh = bid % p.num_kv_heads;  // fastest: one KV head per XCD when Hkv == 8
     bid /= p.num_kv_heads;
-    const int s = bid % p.num_seqs;
+    // The sequence index rotates with the part index: workgroups are dealt to XCDs, and inside an XCD to
+    // its shader engines, round-robin by index, so a fixed map would pin every part of a long sequence
+    // to one engine.
     const int part = bid / p.num_seqs;
+    const int s = (bid % p.num_seqs + part) % p.num_seqs;
     const int n_kv = p.seq_lens[s];
     const int k_lo = part * p.split_len;
     if (k_lo >= n_kv && !(part == 0)) return;  // parts past the end write nothing
@@ -512,8 +515,8 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void decode_seq_kernel(const
     int bid = blockIdx.x;
     const int hb = bid % head_blocks;
     bid /= head_blocks;
-    const int s = bid % p.num_seqs;
     const int part = bid / p.num_seqs;
+    const int s = (bid % p.num_seqs + part) % p.num_seqs;  // rotated: the parts of a sequence spread over XCDs and engines
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int kvh = hb * WAVES + wave;
