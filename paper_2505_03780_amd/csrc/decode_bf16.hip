@@ -611,7 +611,7 @@ __device__ __forceinline__ void merge_pair(const KParams &p, int lane, int s, in
 }
 
 // Where a workgroup's run of chunks starts, for the token-balanced kernels: the batch's 32-key chunks
-// laid end to end are cut into num_wgs equal runs; run w is [x0, x1) and starts `off` chunks into
+// laid end to end are cut into num_wgs runs of equal length (to within one chunk); run w is [x0, x1) and starts `off` chunks into
 // sequence `s`.  Every wavefront works this out on its own (no barrier): lane l sums the chunk counts
 // of a contiguous block of ceil(B / 64) sequences (independent loads, no cross-lane step inside the
 // loop), one 64-wide scan gives the block prefix sums, and a second 64-wide scan over the one block
@@ -620,6 +620,20 @@ __device__ __forceinline__ void merge_pair(const KParams &p, int lane, int s, in
 struct RunStart {
     int total, x0, x1, s, off;
 };
+// [0, total) cut into n runs whose lengths differ by at most one chunk (the first total % n runs are the
+// longer ones): where run w begins, and which run holds chunk c.  (Runs of ceil(total / n) chunks would
+// leave the last workgroups idle and make all others up to one chunk in total / n longer: 5 % at 19.008
+// chunks per workgroup.)
+__device__ __forceinline__ int run_begin(int total, int n, int w)
+{
+    const int q = total / n, rem = total - q * n;
+    return w * q + (w < rem ? w : rem);
+}
+__device__ __forceinline__ int run_of(int total, int n, int c)
+{
+    const int q = total / n, rem = total - q * n, big = rem * (q + 1);
+    return c < big ? c / (q + 1) : rem + (c - big) / (q > 0 ? q : 1);
+}
 __device__ __forceinline__ RunStart locate_run(const KParams &p, int lane, int w, int num_wgs, bool writer, int32_t *prefix_out)
 {
     const int B = p.num_seqs;
@@ -653,9 +667,8 @@ __device__ __forceinline__ RunStart locate_run(const KParams &p, int lane, int w
             }
             if (lane == 0) prefix_out[B] = r.total;
         }
-        const int per_wg = (r.total + num_wgs - 1) / num_wgs;
-        r.x0 = w * per_wg;
-        r.x1 = r.x0 + per_wg < r.total ? r.x0 + per_wg : r.total;
+        r.x0 = run_begin(r.total, num_wgs, w);
+        r.x1 = run_begin(r.total, num_wgs, w + 1);
         if (r.x0 >= r.x1) return r;
         // the block (lane) that holds chunk x0, then the sequence inside the block
         const int blk = __builtin_ctzll(__builtin_amdgcn_ballot_w64(incl > r.x0));
@@ -676,9 +689,8 @@ __device__ __forceinline__ RunStart locate_run(const KParams &p, int lane, int w
         r.total += __builtin_amdgcn_readlane(incl, 63);
     }
     if (writer && lane == 0) prefix_out[B] = r.total;
-    const int per_wg = (r.total + num_wgs - 1) / num_wgs;
-    r.x0 = w * per_wg;
-    r.x1 = r.x0 + per_wg < r.total ? r.x0 + per_wg : r.total;
+    r.x0 = run_begin(r.total, num_wgs, w);
+    r.x1 = run_begin(r.total, num_wgs, w + 1);
     if (r.x0 >= r.x1) return r;
     int base = 0;
     for (int g0 = 0; g0 < B; g0 += 64) {
@@ -765,10 +777,9 @@ __global__ __launch_bounds__(64 * kMergeWaves) void decode_balanced_combine_kern
     const int B = p.num_seqs;
     const int32_t *prefix = (const int32_t *)(p.workspace + (int64_t)(num_wgs + B) * p.num_q_heads * (HD + 2));
     const int c0 = prefix[s], c1 = prefix[s + 1], total = prefix[B];
-    const int per_wg = (total + num_wgs - 1) / num_wgs;
     // an empty context has no piece: parts = 0 makes the merge write zeros
-    const int w0 = c1 > c0 ? c0 / per_wg : 0;
-    const int parts = c1 > c0 ? (c1 - 1) / per_wg - w0 + 1 : 0;
+    const int w0 = c1 > c0 ? run_of(total, num_wgs, c0) : 0;
+    const int parts = c1 > c0 ? run_of(total, num_wgs, c1 - 1) - w0 + 1 : 0;
     if (parts == 1) return;  // the main kernel wrote this sequence itself
     const int64_t stride = (int64_t)p.num_q_heads * (HD + 2);
     merge_pair<HD>(p, lane, s, kvh, pair, p.workspace + (int64_t)(w0 + s) * stride + (int64_t)kvh * p.group * (HD + 2), parts, HD + 2, stride);
