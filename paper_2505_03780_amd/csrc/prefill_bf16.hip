@@ -81,8 +81,13 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_bf16_kernel(const KParams 
     int bid = blockIdx.x;
     const int hg = bid % nhg;  // fastest: workgroups of one KV head land on one XCD when Hkv == 8
     bid /= nhg;
-    const int s = bid % p.num_seqs;
-    const int r = bid / p.num_seqs;  // tile index counted from the END of the sequence (heavy tiles first)
+    // Tile level outermost, counted down from the longest sequence's last tile (costly tiles first, in
+    // every sequence at the same time); the sequence index rotates with the level, because inside an
+    // XCD workgroups are dealt to the four shader engines round-robin by index and a fixed map would
+    // give one engine all tiles of a long sequence.
+    const int q_tiles = (p.max_q_len + C::kTok - 1) / C::kTok;  // the grid's tile dimension
+    const int r = bid / p.num_seqs;
+    const int s = (bid % p.num_seqs + r) % p.num_seqs;
     const int kvh = hg % p.num_kv_heads;
     const int hsub = hg / p.num_kv_heads;
 
@@ -91,8 +96,8 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_bf16_kernel(const KParams 
     const int n_kv = p.seq_lens[s];
     const int off = n_kv - n_q;
     const int n_tiles_q = (n_q + C::kTok - 1) / C::kTok;
-    const int qtile = n_tiles_q - 1 - r;
-    if (qtile < 0) return;
+    const int qtile = q_tiles - 1 - r;
+    if (qtile < 0 || qtile >= n_tiles_q) return;
     const int t0 = qtile * C::kTok;
 
     const int tid = threadIdx.x;
