@@ -223,6 +223,9 @@ def test_rmsnorm_validation_and_selection_on_the_host():
     assert names[A.rmsnorm_selected_instance(_rms(num_tokens=8192))] == "rmsnorm tpr512 vpt1 rows1"
     assert names[A.rmsnorm_selected_instance(_rms(hidden=8192, x_stride=8192, out_stride=8192, residual_stride=8192))] == "rmsnorm tpr1024 vpt1 rows1"
     assert names[A.rmsnorm_selected_instance(_rms(hidden=1024))] == "rmsnorm tpr256 vpt1 rows1"
+    # mid-size calls (tens of MB of traffic, rows of at most 4096): four vectors per lane, 256-lane workgroups
+    assert names[A.rmsnorm_selected_instance(_rms(num_tokens=2048))] == "rmsnorm tpr128 vpt4 rows2"
+    assert names[A.rmsnorm_selected_instance(_rms(num_tokens=8192, hidden=1024))] == "rmsnorm tpr32 vpt4 rows8"
     assert names[A.rmsnorm_selected_instance(_rms(hidden=16384, x_stride=16384, out_stride=16384, residual_stride=16384))] == "rmsnorm tpr1024 vpt2 rows1"
     # every supported hidden size has at least one instance; a forced one that does not fit is refused
     for h in range(8, 16385, 8):
