@@ -65,6 +65,14 @@ def library_path() -> str:
     return _LIB_PATH
 
 
+def use_library(path: str) -> None:
+    """Load another build of the library (the profiling build) instead; only before the first load."""
+    global _LIB_PATH
+    if _lib is not None:
+        raise RuntimeError("the library is already loaded")
+    _LIB_PATH = path
+
+
 def load_library():
     """Load the HIP library.  Raises if it has not been built (python -m paper_2505_03780_amd.build)."""
     global _lib

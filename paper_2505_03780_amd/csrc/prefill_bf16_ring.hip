@@ -135,6 +135,13 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
     constexpr int KSTEPS = kHD / 16;
     constexpr int DB = kHD / 32;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+#ifdef ATTN_RING_PROFILE
+    // Profiling build only: per-wavefront time stamps (100 MHz wall clock) and where the wave ran, written
+    // to the workspace as 16 words per wave: [0..4] cycles per loop phase, [5] units, [6] loop cycles,
+    // [7] clock at the end of the loop, [8] at entry, [9] at the start of the loop, [10] at exit,
+    // [11] block index, [12] hardware id register, [13] XCD id.
+    const unsigned long long prof_entry = wall_clock64();
+#endif
 
     // ---- which (head group, sequence, query tile) ---------------------------------------------
     // Workgroups go to the eight XCDs round-robin, so with the KV head innermost every XCD (and its
@@ -479,6 +486,7 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
 #ifdef ATTN_RING_PROFILE
     unsigned long long prof_t[5] = {0, 0, 0, 0, 0}, prof_last = __builtin_readcyclecounter();
     const unsigned long long prof_begin = prof_last;
+    const unsigned long long prof_loop_begin = wall_clock64();
 #define PROF_MARK(i)                                                   \
     {                                                                  \
         const unsigned long long now = __builtin_readcyclecounter();   \
@@ -606,11 +614,13 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
 
 #ifdef ATTN_RING_PROFILE
     if (lane == 0 && p.workspace) {
-        unsigned long long *dst = (unsigned long long *)p.workspace + ((size_t)blockIdx.x * WAVES + wave) * 8;
+        unsigned long long *dst = (unsigned long long *)p.workspace + ((size_t)blockIdx.x * WAVES + wave) * 16;
         for (int i = 0; i < 5; ++i) dst[i] = prof_t[i];
         dst[5] = n_units;
         dst[6] = __builtin_readcyclecounter() - prof_begin;
         dst[7] = wall_clock64();
+        dst[8] = prof_entry;
+        dst[9] = prof_loop_begin;
     }
 #endif
     // ---- epilogue: O / l, transposed through LDS, whole rows to HBM ------------------------------
@@ -649,6 +659,19 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
         if (t < n_q)
             *(u32x4 *)(obase + (int64_t)(q0 + t) * p.o_stride_tok + (int64_t)head * p.o_stride_head + 8 * chunk) = row;
     }
+#ifdef ATTN_RING_PROFILE
+    wait_vmcnt<0>();
+    if (lane == 0 && p.workspace) {
+        unsigned long long *dst = (unsigned long long *)p.workspace + ((size_t)blockIdx.x * WAVES + wave) * 16;
+        unsigned hw_id, xcc_id;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw_id));
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc_id));
+        dst[10] = wall_clock64();
+        dst[11] = blockIdx.x;
+        dst[12] = hw_id;
+        dst[13] = xcc_id;
+    }
+#endif
 }
 
 template <typename E, int QB, int HPW, int NSLOT, int PF, int WAVES>
