@@ -75,7 +75,7 @@ def report(name, chosen, kernel_us, t) -> str:
     se = (hw >> 13) & 7
     cu = ((hw >> 8) & 15) | (se << 4) | (xcc << 8)
     L = ["# Workgroup lifetimes of the ring prefill kernel: %s" % name, "",
-         "Instance `%s`; one call, %.1f us between HIP events (profiling build: its per-phase cycle counters slow the unit loop by 10-30 %)." % (chosen, kernel_us), "",
+         "Instance `%s`; one call, %.1f us between HIP events (profiling build: its per-phase cycle counters slow the unit loop by 10-30 %%)." % (chosen, kernel_us), "",
          "| per wavefront | mean us | median | 90th percentile | max |", "|---|---|---|---|---|"]
     for lab, x in (("prologue (entry to first loop iteration)", pro), ("unit loop", loop), ("epilogue (last iteration to exit, stores drained)", epi), ("lifetime", life)):
         L.append("| %s | %.2f | %.2f | %.2f | %.2f |" % (lab, x.mean(), np.median(x), np.percentile(x, 90), x.max()))
