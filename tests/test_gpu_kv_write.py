@@ -15,8 +15,8 @@ def _bits(t):
     return t.view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-def _dev(bits):
-    return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+def _dev(bits, dtype=torch.bfloat16):
+    return torch.from_numpy(bits.view(np.int16)).view(dtype).cuda()
 
 
 @pytest.mark.parametrize("T,Hkv,D,bs,nb", [(1, 8, 128, 16, 4), (777, 8, 128, 16, 64), (300, 2, 64, 32, 16), (5000, 8, 128, 16, 400), (64, 1, 8, 128, 2)])
@@ -34,6 +34,15 @@ def test_scatter_matches_the_oracle_bit_for_bit(T, Hkv, D, bs, nb):
     oracle.kv_cache_write(kc, vc, kn, vn, slots)
     np.testing.assert_array_equal(_bits(dk), kc)
     np.testing.assert_array_equal(_bits(dv), vc)
+    # fp16 caches: the same bytes under the other 16-bit element type
+    kc2 = rng.integers(0, 1 << 16, size=(nb, bs, Hkv, D), dtype=np.uint16)
+    vc2 = rng.integers(0, 1 << 16, size=(nb, bs, Hkv, D), dtype=np.uint16)
+    hk, hv = _dev(kc2, torch.float16), _dev(vc2, torch.float16)
+    A.attn_kv_cache_write(_dev(kn, torch.float16), _dev(vn, torch.float16), hk, hv, torch.from_numpy(slots).cuda())
+    torch.cuda.synchronize()
+    oracle.kv_cache_write(kc2, vc2, kn, vn, slots)
+    np.testing.assert_array_equal(_bits(hk), kc2)
+    np.testing.assert_array_equal(_bits(hv), vc2)
 
 
 def test_fp32_elements_strided_sources_and_errors():
