@@ -1,6 +1,7 @@
 """Configuration-portability study on one GPU.
 
     python -m paper_2505_03780_amd.portability --kind decode|prefill [--iters 10] [--out FILE.md]
+                                               [--cache FILE] [--batches 1,16] [--lengths 1024,4096]
 
 The paper's second research question is how far a configuration tuned for one setting carries over
 to another (section "Evaluation": reusing the other platform's configurations costs between 20 % and
@@ -80,7 +81,7 @@ def _time(lib_fn, args, iters):
     return float(np.median([e0.elapsed_time(e1) for e0, e1 in ev])) * 1e3  # microseconds
 
 
-def study(kind: str, iters: int, batches, seqlens):
+def study(kind: str, iters: int, batches, seqlens, cache_path=None):
     import torch
 
     from . import binding as B
@@ -97,7 +98,7 @@ def study(kind: str, iters: int, batches, seqlens):
         a, keep = _bucket_inputs(kind, *bk)
         B.attn_force_instance(is_decode, -1)
         t_heur[bk] = (_time(fn, a, iters), names[B.attn_selected_instance(a, is_decode)])
-        B.attn_tune(a, is_decode, None, iters, 0)
+        B.attn_tune(a, is_decode, cache_path, iters, 0)
         winner[bk] = B.attn_selected_instance(a, is_decode)
         del a, keep
         torch.cuda.empty_cache()
@@ -144,11 +145,16 @@ def main():
     ap.add_argument("--kind", choices=["decode", "prefill"], required=True)
     ap.add_argument("--iters", type=int, default=10)
     ap.add_argument("--out", default=None)
+    ap.add_argument("--cache", default=None, help="also record every bucket's winner in this cache file (ahead-of-time tuning: "
+                                                   "point ATTN_TUNE_CACHE at it later)")
+    ap.add_argument("--batches", default=None, help="comma-separated batch sizes instead of the default grid")
+    ap.add_argument("--lengths", default=None, help="comma-separated sequence lengths instead of the default grid")
     a = ap.parse_args()
+    ints = lambda s, d: d if s is None else [int(x) for x in s.split(",")]
     if a.kind == "decode":
-        text = study("decode", a.iters, [1, 16, 64, 256], [1024, 4096, 16384])
+        text = study("decode", a.iters, ints(a.batches, [1, 16, 64, 256]), ints(a.lengths, [1024, 4096, 16384]), a.cache)
     else:
-        text = study("prefill", a.iters, [1, 8, 64], [512, 1024, 2048, 8192])
+        text = study("prefill", a.iters, ints(a.batches, [1, 8, 64]), ints(a.lengths, [512, 1024, 2048, 8192]), a.cache)
     print(text)
     if a.out:
         open(a.out, "w").write(text)
