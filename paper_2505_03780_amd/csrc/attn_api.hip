@@ -207,14 +207,14 @@ void apply_split(KParams &p, const Instance &inst)
 }
 
 // ---- built-in heuristic (used until a bucket has been tuned) -----------------------------------
-int find_instance(int is_decode, const KParams &p, int waves, int hpw, int bn, int bm, int split_len, int variant = 0)
+int find_instance(int is_decode, const KParams &p, int waves, int hpw, int bn, int bm, int split_len, int variant = 0, int stages = 0)
 {
     int n;
     const Instance *t = instances(is_decode, &n);
     for (int i = 0; i < n; ++i) {
         if (!t[i].valid(p)) continue;
         if (t[i].waves == waves && t[i].heads_per_wg == hpw && t[i].block_n == bn && (bm <= 0 || t[i].block_m == bm) &&
-            t[i].split_len == split_len && t[i].variant == variant)
+            t[i].split_len == split_len && t[i].variant == variant && (stages <= 0 || t[i].stages == stages))
             return i;
     }
     return -1;
@@ -236,7 +236,10 @@ int heuristic(const KParams &p, int is_decode)
         // Short sequences: two small workgroups per compute unit hide each other's prologue and
         // epilogue; long ones: one large workgroup with the deeper ring.
         const bool small_wg = p.max_kv_len <= 2048;
-        id = find_instance(0, p, small_wg ? 4 : 8, hpw, 32, small_wg ? 128 : 256, 0, order);  // LDS-ring kernel (D = 128)
+        // a paged context adds the table entry to every transfer's address chain: the deepest prefetch
+        // (8 units) measured up to 10 % ahead of 5 on the slower machines there, level elsewhere
+        if (!small_wg && p.block_table) id = find_instance(0, p, 8, hpw, 32, 256, 0, order, 8);
+        if (id < 0) id = find_instance(0, p, small_wg ? 4 : 8, hpw, 32, small_wg ? 128 : 256, 0, order);  // LDS-ring kernel (D = 128)
         if (id < 0) id = find_instance(0, p, 8, hpw, 32, 256, 0, order);
         if (id < 0) id = find_instance(0, p, 4, hpw, 32, 256, 0, order);
         if (id < 0) id = find_instance(0, p, 4, hpw, 64, 64 * 4, 0);  // register-staged kernel

@@ -254,7 +254,11 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
     const unsigned char *kbase = (const unsigned char *)p.k + (int64_t)kvh * p.kv_stride_head * 2;
     const unsigned char *vbase = (const unsigned char *)p.v + (int64_t)kvh * p.kv_stride_head * 2;
     const int kv0 = PAGED ? 0 : p.kv_start_loc[s];
-    const int32_t *bt_row = PAGED ? p.block_table + (int64_t)s * p.block_table_stride : nullptr;
+    // The block table is read through the scalar cache (constant address space): a vector load would
+    // share the counter of the LDS transfers, and waiting for it would drain the whole transfer queue
+    // once per unit.
+    typedef const __attribute__((address_space(4))) int32_t *table_ptr;
+    const table_ptr bt_row = PAGED ? (table_ptr)(p.block_table + (int64_t)s * p.block_table_stride) : (table_ptr) nullptr;
     constexpr int RPW = C::kRowsPerWave, NDMA = C::kDmaPerWave;
     const int dma_row = RPW * wave + (lane >> 4);  // + 4*i, row inside the unit
     const uint32_t tok_bytes = (uint32_t)p.kv_stride_tok * 2;
@@ -268,7 +272,7 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
         int u0 = unit * kUnit < last_unit0 ? unit * kUnit : last_unit0;
         int row = u0 + RPW * wave;
         row = row < n_kv ? row : n_kv - 1;
-        return __builtin_amdgcn_readfirstlane(bt_row[row >> p.block_shift]);
+        return bt_row[__builtin_amdgcn_readfirstlane(row) >> p.block_shift];
     };
     auto issue_unit = [&](int unit, int entry) {
         unsigned char *slot = lds + (unit % NSLOT) * kSlotBytes + RPW * wave * 256;

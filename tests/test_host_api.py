@@ -115,6 +115,11 @@ def test_instance_tables_and_heuristic_selection():
     assert "hpw4" in names_p[i] and "w8" in names_p[i] and "seqmajor" in names_p[i]
     i = A.attn_selected_instance(_paged(max_kv_len=1536, max_q_len=512), False)  # a cached prefix twice the chunk
     assert "seqmajor" in names_p[i]
+    # a long paged context: the large ring with the deepest prefetch (the table entry lengthens the address chain)
+    i = A.attn_selected_instance(_paged(max_kv_len=8704, max_q_len=512, block_table_stride=544), False)
+    assert names_p[i] == "prefill_bf16_ring d128 qb1 w8 hpw4 slots8 pf8 seqmajor"
+    i = A.attn_selected_instance(_args(max_kv_len=8192, max_q_len=8192), False)
+    assert names_p[i] == "prefill_bf16_ring d128 qb1 w8 hpw4 slots8 pf5 seqmajor"
     # MHA cannot
     i = A.attn_selected_instance(_args(num_kv_heads=32), False)
     assert "hpw1" in names_p[i]
