@@ -518,21 +518,25 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) sum[qb] = 0.f;
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        // weights 2p, 2p+1 of row block qb: exponentials, rounding, row sum.  The exponentials are spread over
+        // both phases (half under the score MFMAs, half under the first PV MFMAs, which only need the
+        // first half), so that neither phase has more vector work than matrix work to hide it under.
+        auto exp_pair = [&](int qb, int pair) {
+            const int v = 2 * pair;
+            const float e0 = fast_exp2(CUR_MASK ? cur[qb][v] - m_ref[qb] : __builtin_fmaf(cur[qb][v], c, -m_ref[qb]));
+            const float e1 = fast_exp2(CUR_MASK ? cur[qb][v + 1] - m_ref[qb] : __builtin_fmaf(cur[qb][v + 1], c, -m_ref[qb]));
+            x2 pr;
+            pr[0] = (elem)e0;
+            pr[1] = (elem)e1;
+            sum[qb] = E::dot2(pr, ones, sum[qb]);
+            pf[qb][v >> 3][v & 7] = pr[0];
+            pf[qb][v >> 3][(v & 7) + 1] = pr[1];
+        };
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const int ks = g / QB, qb = g % QB;
             nxt[qb] = E::mfma(kf[ks], qf[qb][ks], ks == 0 ? zero : nxt[qb]);
-            {
-                const int v = 2 * (g / QB);
-                const float e0 = fast_exp2(CUR_MASK ? cur[qb][v] - m_ref[qb] : __builtin_fmaf(cur[qb][v], c, -m_ref[qb]));
-                const float e1 = fast_exp2(CUR_MASK ? cur[qb][v + 1] - m_ref[qb] : __builtin_fmaf(cur[qb][v + 1], c, -m_ref[qb]));
-                x2 pr;
-                pr[0] = (elem)e0;
-                pr[1] = (elem)e1;
-                sum[qb] = E::dot2(pr, ones, sum[qb]);
-                pf[qb][v >> 3][v & 7] = pr[0];
-                pf[qb][v >> 3][(v & 7) + 1] = pr[1];
-            }
+            if (ks % 2 == 0) exp_pair(qb, ks / 2);  // weights of keys 0..15: the B operand of the first four PV MFMAs
             if (g * 8 / G != (g + 1) * 8 / G) {
                 const int f = g * 8 / G;
                 vfrag[f] = *(const x8 *)(img + f * 1024);
@@ -540,8 +544,6 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
             if (g == 1) transpose_load(u + 1, raw);  // this wave's share of V(u+1), stored late in phase Y
             __builtin_amdgcn_sched_barrier(0);
         }
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) l_run[qb] += sum[qb];
         PROF_MARK(0)
 
         float mx[QB];
@@ -552,7 +554,8 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
         for (int g = 0; g < G; ++g) {
             const int f = g / QB, qb = g % QB;  // f = ks2 * DB + db
             oacc[qb][f % DB] = E::mfma(vfrag[f], pf[qb][f / DB], oacc[qb][f % DB]);
-            const int sl = g - 2;  // the first two groups leave the last S MFMAs time to drain
+            if (f < DB) exp_pair(qb, 4 + f);  // weights of keys 16..31, needed from the fifth PV MFMA on
+            const int sl = g - 4 * QB;  // the second half of the phase: the last S MFMAs have drained
             if (sl >= 0 && sl < 4 * QB) {
                 const int q2 = sl / 4, v0 = 4 * (sl % 4);
                 if (NXT_MASK) {
@@ -574,6 +577,8 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
             if (g == G - 2) transpose_store(u + 1, raw);  // image (u+1)&1 was last read in iteration u-1
             __builtin_amdgcn_sched_barrier(0);
         }
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) l_run[qb] += sum[qb];
         PROF_MARK(1)
         float bm[QB];
 #pragma unroll
