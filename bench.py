@@ -35,10 +35,10 @@ WORKLOADS = {"c2": 2, "c3": 3, "c4": 4, "c5": 5}
 # commands are in profiles/hbm_traffic_all_workloads_pmc.md.  Keyed by workload and kernel family:
 # a run that selects another family reports null.
 MEASURED_TRAFFIC_BYTES = {
-    ("c2_decode_8b", "decode_bf16_balanced"): (2 * (311624 + 2599) + 4973 + 512) * 1024,
-    ("c5_decode_70b_long", "decode_bf16_balanced"): (2 * (756729 + 4479) + 8679 + 256) * 1024,
-    ("c3_prefill_8b", "prefill_bf16_ring"): (2 * 79633 + 70104) * 1024,
-    ("c4_chunked_prefill", "prefill_bf16_ring seqmajor"): (2 * 216760 + 65536) * 1024,
+    ("c2_decode_8b", "decode_bf16_balanced"): (2 * (311630 + 2690) + 5152 + 512) * 1024,
+    ("c5_decode_70b_long", "decode_bf16_balanced"): (2 * (756726 + 4546) + 8809 + 256) * 1024,
+    ("c3_prefill_8b", "prefill_bf16_ring"): (2 * 78890 + 70104) * 1024,
+    ("c4_chunked_prefill", "prefill_bf16_ring seqmajor"): (2 * 212289 + 65536) * 1024,
     ("rmsnorm_8b_t8192_h4096", "rmsnorm"): (2 * 65585 + 131131) * 1024,
 }
 
