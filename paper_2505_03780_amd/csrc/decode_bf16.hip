@@ -650,19 +650,22 @@ __device__ __forceinline__ RunStart locate_run(const KParams &p, int lane, int w
         const int R = (B + 63) / 64;  // sequences per lane
         int mine = 0;
 #pragma unroll 8
-        for (int k = 0; k < R; ++k) {  // unrolled so that the loads of a batch are in flight together
-            const int i = lane * R + k;
-            mine += i < B ? (p.seq_lens[i] + kChunk - 1) / kChunk : 0;
+        for (int k = 0; k < R; ++k) {  // unrolled, and every load unconditional (index clamped, value masked), so
+            const int i = lane * R + k;  // that the loads of a batch of eight are in flight together
+            const int len = p.seq_lens[i < B ? i : B - 1];
+            mine += ((len + kChunk - 1) / kChunk) & -(int)(i < B);  // masked by arithmetic: a select would become a branch around the load
         }
         const int incl = scan64(mine);
         r.total = __builtin_amdgcn_readlane(incl, 63);
         if (writer) {
             int run = incl - mine;
+#pragma unroll 8
             for (int k = 0; k < R; ++k) {
                 const int i = lane * R + k;
+                const int len = p.seq_lens[i < B ? i : B - 1];
                 if (i < B) {
                     prefix_out[i] = run;
-                    run += (p.seq_lens[i] + kChunk - 1) / kChunk;
+                    run += (len + kChunk - 1) / kChunk;
                 }
             }
             if (lane == 0) prefix_out[B] = r.total;
@@ -674,7 +677,8 @@ __device__ __forceinline__ RunStart locate_run(const KParams &p, int lane, int w
         const int blk = __builtin_ctzll(__builtin_amdgcn_ballot_w64(incl > r.x0));
         const int base = __builtin_amdgcn_readlane(incl - mine, blk);
         const int i2 = blk * R + lane;
-        const int c2 = (lane < R && i2 < B) ? (p.seq_lens[i2] + kChunk - 1) / kChunk : 0;
+        const int len2 = p.seq_lens[i2 < B ? i2 : B - 1];
+        const int c2 = (lane < R && i2 < B) ? (len2 + kChunk - 1) / kChunk : 0;
         const int incl2 = scan64(c2);
         const int j = __builtin_ctzll(__builtin_amdgcn_ballot_w64(base + incl2 > r.x0));
         r.s = blk * R + j;
