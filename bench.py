@@ -28,24 +28,120 @@ HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
 WORKLOADS = {"c2": 2, "c3": 3, "c4": 4, "c5": 5}
+GRAPH_REPLAYS = 3  # timed replays of the K-step graph; the median one is reported
 
-# HBM bytes per call measured with rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE (separate runs, KiB
-# per dispatch summed over the kernels of one call), each scaled by what the same counter reads for a
-# 1 GiB device copy (FETCH_SIZE reads 0.5 KiB per KiB fetched, WRITE_SIZE 1.0); the summary and the
-# commands are in profiles/hbm_traffic_all_workloads_pmc.md.  Keyed by workload and kernel family:
-# a run that selects another family reports null.
-MEASURED_TRAFFIC_BYTES = {
-    ("c2_decode_8b", "decode_bf16_balanced"): (2 * (311630 + 2690) + 5152 + 512) * 1024,
-    ("c5_decode_70b_long", "decode_bf16_balanced"): (2 * (756726 + 4546) + 8809 + 256) * 1024,
-    ("c3_prefill_8b", "prefill_bf16_ring"): (2 * 78890 + 70104) * 1024,
-    ("c4_chunked_prefill", "prefill_bf16_ring seqmajor"): (2 * 212289 + 65536) * 1024,
-    ("rmsnorm_8b_t8192_h4096", "rmsnorm"): (2 * 65585 + 131131) * 1024,
-}
+TRAFFIC_JSON = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+PROBE_LIB = os.path.join(ROOT, "paper_2505_03780_amd", "libprobe_gfx950.so")
 
 
 def _traffic(wl_name: str, instance: str):
-    family = instance.split(" ")[0] + (" seqmajor" if instance.endswith("seqmajor") else "")
-    return MEASURED_TRAFFIC_BYTES.get((wl_name, family))
+    """HBM bytes per call of this workload, measured with rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
+    (separate runs), each scaled by what the same counter reads for a 1 GiB device copy; written to
+    profiles/hbm_traffic.json by `bench.py --summarize-traffic` (commands and tables in
+    profiles/hbm_traffic_all_workloads_pmc.md).  The figure belongs to the instance it was measured
+    with: a run that times another instance reports null and says so on stderr."""
+    try:
+        with open(TRAFFIC_JSON) as f:
+            table = json.load(f)
+    except (OSError, ValueError) as e:
+        print("bench.py: %s unreadable (%r): roofline.traffic is null" % (TRAFFIC_JSON, e), file=sys.stderr)
+        return None
+    rec = table.get(wl_name)
+    if rec is None:
+        print("bench.py: no traffic record for %s in %s: roofline.traffic is null" % (wl_name, TRAFFIC_JSON), file=sys.stderr)
+        return None
+    if rec["instance"] != instance:
+        print("bench.py: traffic of %s was measured on '%s', this run timed '%s': roofline.traffic is null" % (
+            wl_name, rec["instance"], instance), file=sys.stderr)
+        return None
+    return int(rec["bytes_per_call"])
+
+
+def summarize_traffic(directory: str, workload: str):
+    """Reads the four rocprofv3 --pmc runs under `directory` (probe_FETCH_SIZE, run_FETCH_SIZE,
+    probe_WRITE_SIZE, run_WRITE_SIZE: counter_collection.csv files; the run_* logs hold the bench
+    line with the instance that ran) and records the workload's HBM bytes per call in
+    profiles/hbm_traffic.json."""
+    import csv
+    import glob
+
+    def per_dispatch(sub, want):
+        agg = {}
+        for fn in glob.glob(os.path.join(directory, sub, "**", "*counter_collection.csv"), recursive=True):
+            for r in csv.DictReader(open(fn)):
+                if want(r["Kernel_Name"]):
+                    a = agg.setdefault(r["Kernel_Name"], [0.0, 0])
+                    a[0] += float(r["Counter_Value"])
+                    a[1] += 1
+        return {k: v[0] / v[1] for k, v in agg.items()}
+
+    ours = lambda n: "attn::" in n
+    copy = lambda n: "copyBuffer" in n
+    out = {}
+    for counter in ("FETCH_SIZE", "WRITE_SIZE"):
+        probe = per_dispatch("probe_" + counter, copy)
+        if not probe:
+            raise SystemExit("no copy kernel under %s/probe_%s" % (directory, counter))
+        factor = float(1 << 20) / (sum(probe.values()) / len(probe))  # true KiB per counted KiB
+        out[counter] = {"factor": factor, "kernels": {k: v for k, v in per_dispatch("run_" + counter, ours).items()}}
+    line = None
+    for l in open(os.path.join(directory, "run_FETCH_SIZE.log")):
+        if l.startswith("{") and '"metric"' in l:
+            line = json.loads(l)
+    if line is None:
+        raise SystemExit("no bench line in run_FETCH_SIZE.log")
+    name, instance = line["config"]["workload"], line["config"]["instance"]
+    total = sum(out[c]["factor"] * sum(out[c]["kernels"].values()) for c in out) * 1024.0
+    try:
+        table = json.load(open(TRAFFIC_JSON))
+    except (OSError, ValueError):
+        table = {}
+    table[name] = {"instance": instance, "bytes_per_call": int(round(total)),
+                   "fetch_KiB_per_dispatch": out["FETCH_SIZE"]["kernels"], "fetch_factor": out["FETCH_SIZE"]["factor"],
+                   "write_KiB_per_dispatch": out["WRITE_SIZE"]["kernels"], "write_factor": out["WRITE_SIZE"]["factor"]}
+    with open(TRAFFIC_JSON, "w") as f:
+        json.dump(table, f, indent=1, sort_keys=True)
+        f.write("\n")
+    print(json.dumps({name: table[name]}, indent=1))
+
+
+def probe_achievable(read_bytes: int = 1 << 31, mfma_iters: int = 1 << 14) -> dict:
+    """Times the two probes of libprobe_gfx950.so (a library of its own, outside the attention ABI) on
+    the current stream: sustained HBM read bandwidth (GB/s) and sustained bf16 MFMA rate (TFLOP/s)."""
+    import ctypes
+
+    import torch
+
+    if not os.path.exists(PROBE_LIB):
+        raise ImportError("%s is missing: build it with `python -m paper_2505_03780_amd.build`" % PROBE_LIB)
+    lib = ctypes.CDLL(PROBE_LIB)
+    lib.probe_hbm_read.restype = ctypes.c_int
+    lib.probe_hbm_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+    lib.probe_mfma_bf16.restype = ctypes.c_int64
+    lib.probe_mfma_bf16.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    buf = torch.zeros(read_bytes // 4, dtype=torch.int32, device="cuda")
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    sp = int(torch.cuda.current_stream().cuda_stream)
+    out = {}
+    for name in ("hbm_read_GBps", "mfma_bf16_TFLOPs"):
+        best = 0.0
+        for rep in range(4):  # the first repetition warms clocks and caches
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            if name == "hbm_read_GBps":
+                rc = lib.probe_hbm_read(buf.data_ptr(), read_bytes, sink.data_ptr(), sp)
+                work = float(read_bytes) / 1e9
+            else:
+                rc = lib.probe_mfma_bf16(mfma_iters, sink.data_ptr(), sp)
+                work = float(rc) / 1e12
+            if rc < 0:
+                raise RuntimeError("probe failed: %d" % rc)
+            e1.record()
+            torch.cuda.synchronize()
+            if rep:
+                best = max(best, work / (e0.elapsed_time(e1) * 1e-3))
+        out[name] = best
+    return out
 
 
 def _dev(a):
@@ -137,14 +233,19 @@ def time_steps(run: Runner, steps: int, warmup: int):
                 run.step(side.cuda_stream)
         g.replay()
         torch.cuda.synchronize()
-        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t0 = time.perf_counter()
-        g0.record(stream)
-        g.replay()
-        g1.record(stream)
-        torch.cuda.synchronize()
-        graph_ms = (time.perf_counter() - t0) * 1e3 / steps
-        graph_ev_ms = g0.elapsed_time(g1) / steps
+        # three timed replays of the same K steps; the median replay is reported (one replay of 20
+        # steps moves by a few percent from run to run)
+        reps = []
+        for _ in range(GRAPH_REPLAYS):
+            g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t0 = time.perf_counter()
+            g0.record(stream)
+            g.replay()
+            g1.record(stream)
+            torch.cuda.synchronize()
+            reps.append(((time.perf_counter() - t0) * 1e3 / steps, g0.elapsed_time(g1) / steps))
+        reps.sort(key=lambda r: r[1])
+        graph_ms, graph_ev_ms = reps[len(reps) // 2]
         del g
     except Exception as e:  # keep the eager figure if capture is unavailable
         print("bench.py: graph timing skipped: %r" % (e,), file=sys.stderr)
@@ -157,7 +258,7 @@ def time_steps(run: Runner, steps: int, warmup: int):
 def _figures(wl, run, wall_ms, ev_mean_ms, ev_med_ms, eager_ms, eager_ev_ms, graphed):
     res = {"workload": wl.name, "instance": run.instance, "ms_per_step": wall_ms, "kernel_ms_mean": ev_mean_ms,
            "kernel_ms_median_eager": ev_med_ms, "kernel_ms_mean_eager": eager_ev_ms, "ms_per_step_eager": eager_ms,
-           "timed_as": "one HIP graph of all steps" if graphed else "eager launches"}
+           "timed_as": ("one HIP graph of all steps, median of %d replays" % GRAPH_REPLAYS) if graphed else "eager launches"}
     if wl.kind == "decode":
         nbytes = wl.algorithmic_bytes()
         ach = nbytes / (ev_mean_ms * 1e-3) / 1e9
@@ -173,7 +274,41 @@ def _figures(wl, run, wall_ms, ev_mean_ms, ev_med_ms, eager_ms, eager_ev_ms, gra
     return res
 
 
-def measure(wl_id: int, steps: int, warmup: int, tune: bool):
+def check_output(wl, run: "Runner"):
+    """After timing, outside the timed region: what the timed instance left in the output buffer,
+    against the fp64 oracle.  Decode: every output row.  Prefill: one row per query head and run of
+    32 tokens of every sequence (workloads.stratified_rows), so no workgroup of any tile size escapes."""
+    import oracle
+    import workloads as W
+
+    torch = run.torch
+    torch.cuda.synchronize()
+    f16 = wl.dtype == "f16"
+    wide = (lambda a: a.astype(np.float32)) if f16 else (lambda a: a)
+    prob = oracle.OracleProblem(wide(wl.q), wide(wl.k), wide(wl.v), wl.query_start_loc, wl.seq_lens, wl.scale, wl.causal,
+                                block_table=wl.block_table, kv_start_loc=wl.kv_start_loc)
+    if wl.kind == "decode":
+        B, H = wl.num_seqs, wl.num_q_heads
+        seqs = np.repeat(np.arange(B, dtype=np.int32), H)
+        toks = np.zeros(B * H, np.int32)
+        heads = np.tile(np.arange(H, dtype=np.int32), B)
+    else:
+        seqs, toks, heads = W.stratified_rows(wl, 32)
+    ref = oracle.attention_rows(prob, seqs, toks, heads)
+    rows = torch.from_numpy(wl.query_start_loc[seqs].astype(np.int64) + toks).cuda()
+    got = run.out[rows, torch.from_numpy(heads.astype(np.int64)).cuda()].float().cpu().numpy().astype(np.float64)
+    d = got - ref
+    max_abs = float(np.max(np.abs(d)))
+    rel_rms = float(np.sqrt(np.sum(d * d) / np.sum(ref * ref)))
+    ok = bool(np.isfinite(got).all() and max_abs <= 2e-2 and rel_rms <= 5e-3)
+    if not ok:
+        print("bench.py: %s: the timed instance '%s' is outside the tolerance: max-abs %.3e rel-RMS %.3e" % (
+            wl.name, run.instance, max_abs, rel_rms), file=sys.stderr)
+    return {"rows": int(len(seqs)), "of_rows": int(wl.q.shape[0] * wl.num_q_heads), "max_abs": max_abs, "rel_rms": rel_rms,
+            "tol": [2e-2, 5e-3], "ok": ok, "against": "fp64 oracle, after timing"}
+
+
+def measure(wl_id: int, steps: int, warmup: int, tune: bool, check: bool = True):
     """Times the workload with the instance a user gets after attn_tune on this batch's lengths (the
     paper's thesis: tune ahead of time, then only look up).  The untuned figure (built-in heuristic)
     is measured first, with fewer steps, and reported next to it."""
@@ -197,6 +332,7 @@ def measure(wl_id: int, steps: int, warmup: int, tune: bool):
         run.instance = run.A.attn_instance_name(run.is_decode, run.A.attn_selected_instance(run.args[0], run.is_decode))
     res = _figures(wl, run, *time_steps(run, steps, warmup))
     res["untuned"] = untuned
+    res["check"] = check_output(wl, run) if check else None
     if wl.kind == "decode":
         # a note next to the headline: the same steps always on ONE copy of the KV pool, which the
         # 256 MB last-level cache may partly hold from the step before (the headline rotates two copies)
@@ -207,15 +343,15 @@ def measure(wl_id: int, steps: int, warmup: int, tune: bool):
     return wl, res
 
 
-def measure_rmsnorm(steps: int, warmup: int, tune: bool):
-    """The paper's second kernel, fused residual add + RMS norm at the 8B model's hidden size over a
-    prefill-sized batch of tokens: HBM-bound, reported as algorithmic GB/s."""
+def measure_rmsnorm(steps: int, warmup: int, tune: bool, hidden: int = 4096):
+    """The paper's second kernel, fused residual add + RMS norm at the 8B (hidden 4096) or 70B (8192)
+    model's hidden size over a prefill-sized batch of tokens: HBM-bound, reported as algorithmic GB/s."""
     import torch
 
     import paper_2505_03780_amd as A
     import workloads as W
 
-    wl = W.rmsnorm_8b_prefill()
+    wl = W.rmsnorm_8b_prefill() if hidden == 4096 else W.rmsnorm_70b_prefill()
     x, res, w = _dev(wl.x), _dev(wl.residual), _dev(wl.weight)
     # two sets of buffers take turns, so that a step never finds its rows in the last-level cache
     sets = [(x, res, torch.empty_like(x)), (x.clone(), res.clone(), torch.empty_like(x))]
@@ -243,19 +379,22 @@ def measure_rmsnorm(steps: int, warmup: int, tune: bool):
         loop(steps, side.cuda_stream)
     g.replay()
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record(stream)
-    g.replay()
-    e1.record(stream)
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
-    ev_ms = e0.elapsed_time(e1) / steps
+    reps = []
+    for _ in range(GRAPH_REPLAYS):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(stream)
+        g.replay()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        reps.append(((time.perf_counter() - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps))
+    reps.sort(key=lambda r: r[1])
+    wall_ms, ev_ms = reps[len(reps) // 2]
     nbytes = wl.algorithmic_bytes()
     ach = nbytes / (ev_ms * 1e-3) / 1e9
     return {"workload": wl.name, "instance": inst, "untuned_instance": untuned, "metric": "rmsnorm_hbm_GBps", "unit": "GB/s",
             "value": nbytes / (wall_ms * 1e-3) / 1e9, "ms_per_step": wall_ms, "kernel_ms_mean": ev_ms, "algorithmic_bytes": nbytes,
-            "timed_as": "one HIP graph of all steps",
+            "timed_as": "one HIP graph of all steps, median of %d replays" % GRAPH_REPLAYS,
             "roofline": {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBPS,
                          "traffic": _traffic(wl.name, inst)}}
 
@@ -310,12 +449,19 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-tune", action="store_true", help="keep the built-in heuristic (default: attn_tune runs first, untimed)")
+    ap.add_argument("--no-check", action="store_true", help="skip the oracle check of the timed outputs")
+    ap.add_argument("--summarize-traffic", metavar="DIR",
+                    help="no GPU work: read the rocprofv3 --pmc runs under DIR (see profiles/hbm_traffic_all_workloads_pmc.md) "
+                         "and record the workload's HBM bytes per call in profiles/hbm_traffic.json")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run a 1 GiB device-to-device copy three times (calibrates the FETCH_SIZE / WRITE_SIZE counters)")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU only (one MI355X, no collectives); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if a.summarize_traffic:
+        summarize_traffic(a.summarize_traffic, a.workload)
+        return
     import torch
 
     if not torch.cuda.is_available():
@@ -338,11 +484,10 @@ def main():
                           "dtype": "bf16", "data": "synthetic", "config": {"workload": r["workload"], "instance": r["instance"]},
                           "kernel_ms_mean": r["kernel_ms_mean"], "roofline": r["roofline"]}), flush=True)
         return
-    wl, main_res = measure(WORKLOADS[a.workload], a.steps, a.warmup, not a.no_tune)
-    # what this machine sustains for the two bounding resources (the library's own probes), next to
+    wl, main_res = measure(WORKLOADS[a.workload], a.steps, a.warmup, not a.no_tune, not a.no_check)
+    # what this machine sustains for the two bounding resources (the benchmark's own probes), next to
     # the published peaks the roofline fractions are quoted against
-    import paper_2505_03780_amd as A
-    achievable = A.probe_achievable()
+    achievable = probe_achievable()
 
     def _with_achievable(roof):
         ref = achievable["hbm_read_GBps"] if roof["bound"] == "hbm" else achievable["mfma_bf16_TFLOPs"]
@@ -361,6 +506,7 @@ def main():
         "kernel_ms_mean": main_res["kernel_ms_mean"], "kernel_ms_mean_eager": main_res["kernel_ms_mean_eager"],
         "ms_per_step_eager": main_res["ms_per_step_eager"], "timed_as": main_res["timed_as"],
         "roofline": main_res["roofline"], "untuned": main_res["untuned"], "achievable": achievable,
+        "check": main_res["check"],
     }
     if "hot_cache_note" in main_res:
         line["hot_cache_note"] = main_res["hot_cache_note"]
@@ -373,13 +519,15 @@ def main():
             if name == a.workload:
                 continue
             torch.cuda.empty_cache()
-            _, r = measure(wid, max(5, a.steps // 2), max(2, a.warmup // 2), not a.no_tune)
+            _, r = measure(wid, max(5, a.steps // 2), max(2, a.warmup // 2), not a.no_tune, not a.no_check)
             extra[name] = {k: r[k] for k in ("workload", "instance", "metric", "value", "unit", "ms_per_step", "ms_per_step_eager", "timed_as",
-                                             "kernel_ms_mean", "roofline", "untuned")}
+                                             "kernel_ms_mean", "roofline", "untuned", "check")}
             extra[name]["roofline"] = _with_achievable(extra[name]["roofline"])
         torch.cuda.empty_cache()
-        extra["rmsnorm"] = measure_rmsnorm(a.steps, a.warmup, not a.no_tune)
-        extra["rmsnorm"]["roofline"] = _with_achievable(extra["rmsnorm"]["roofline"])
+        for key, hidden in (("rmsnorm", 4096), ("rmsnorm_h8192", 8192)):
+            extra[key] = measure_rmsnorm(a.steps, a.warmup, not a.no_tune, hidden)
+            extra[key]["roofline"] = _with_achievable(extra[key]["roofline"])
+            torch.cuda.empty_cache()
         line["extra"] = extra
     print(json.dumps(line), flush=True)
 

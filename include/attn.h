@@ -98,7 +98,8 @@ typedef struct attn_args {
     const int32_t *seq_lens;        /* int32 [B]: keys of sequence s = cached prefix + new tokens, already stored */
 
     float scale;    /* softmax scale applied to q.k (1/sqrt(D) for standard attention) */
-    int32_t causal; /* 1: query i sees keys j <= (seq_lens[s] - n_q(s)) + i (bottom-right aligned); 0: all keys */
+    int32_t causal; /* 1: query i sees keys j <= (seq_lens[s] - n_q(s)) + i (bottom-right aligned); 0: all keys.
+                     * Requires seq_lens[s] >= n_q(s); a query that would sit before key 0 gets zeros. */
 
     void *workspace; /* device scratch for split-K partials; may be NULL if attn_workspace_bytes() == 0 */
     uint64_t workspace_bytes;
@@ -121,7 +122,7 @@ int attn_prefill_varlen(const attn_args *args, void *hip_stream);
  * paper cites PagedAttention for this setting; layout above).  Long contexts
  * are split along the key axis; each part writes an fp32 (max, sum, partial
  * output) triple into `workspace` and a second kernel merges them.  The caller
- * provides at least attn_workspace_bytes(args, 1) bytes.  bf16 only.
+ * provides at least attn_workspace_bytes(args, 1) bytes, 8-byte aligned.  dtype ATTN_BF16 or ATTN_F16.
  */
 int attn_decode_paged(const attn_args *args, void *hip_stream);
 
@@ -154,9 +155,12 @@ typedef struct attn_kv_write_args {
 int attn_kv_cache_write(const attn_kv_write_args *args, void *hip_stream);
 
 /*
- * Bytes of workspace the call described by `args` may use (pure host function;
- * pointer fields are ignored).  is_decode = 1 for attn_decode_paged.
- * Returns 0 when args is NULL or malformed.
+ * Bytes of workspace the call described by `args` may use (pure host function apart from one
+ * device-property query; pointer fields are ignored): the largest need of any kernel instance that
+ * may be chosen for it, whatever the winner cache holds.  Fixed-split instances cut a context into at
+ * most 64 parts and a batch into at most two parts per compute unit; the token-balanced ones use one
+ * record per workgroup (at most four per compute unit) and per sequence.  is_decode = 1 for
+ * attn_decode_paged.  Returns 0 when args is NULL or malformed.
  */
 size_t attn_workspace_bytes(const attn_args *args, int is_decode);
 
@@ -175,8 +179,11 @@ size_t attn_workspace_bytes(const attn_args *args, int is_decode);
  * `iters` (<= 0: a default) of the best three; an instance three times slower
  * than the best so far is dropped after one launch; the built-in choice wins
  * ties within 2 % (launch-to-launch noise).  The call records the
- * fastest instance and, if cache_path is not NULL, merges it into that file
- * (atomic replace).  Synchronous; not capturable.
+ * fastest instance and, if cache_path is not NULL, merges it into that file:
+ * read, change and replace (write to a temporary file, fsync, rename) under an
+ * exclusive flock on "<cache_path>.lock", so concurrent tuners keep each other's
+ * lines; damaged lines are dropped, other environments' lines kept.  Synchronous;
+ * not capturable.
  * flags: bit 0 = print one line per measurement to stderr; bit 1 = exhaustive
  * sweep (`iters` launches of every valid instance) instead of the halving.
  */
@@ -188,9 +195,10 @@ int attn_tune(const attn_args *shape_like, int is_decode, const char *cache_path
 int attn_environment_key(char *buf, size_t buf_bytes);
 
 /* Load winners from a cache file written by attn_tune.  Entries recorded for a different device,
- * CU count, runtime or library build are skipped.  Also done lazily from $ATTN_TUNE_CACHE on the first hot
- * call.  A missing or corrupt file returns ATTN_ERR_CACHE_IO and leaves the built-in heuristic in
- * force; hot calls never fail because of the cache. */
+ * CU count, runtime or library build are skipped, and so is a line that does not parse (the lines
+ * around it still count).  Also done lazily from $ATTN_TUNE_CACHE on the first hot call.  A file that
+ * is missing, does not start with the format's first line, or holds nothing but damaged lines returns
+ * ATTN_ERR_CACHE_IO and leaves the built-in heuristic in force; hot calls never fail because of the cache. */
 int attn_load_cache(const char *cache_path);
 
 /* Forget all cached winners (hot calls fall back to the built-in heuristic). */
@@ -198,26 +206,15 @@ void attn_clear_cache(void);
 
 /* Introspection for the tuner and the tests (pure host functions). */
 int attn_num_instances(int is_decode);
-/* Writes a NUL-terminated description ("prefill_bf16 bm=.. bn=.. ...") of instance `id`;
- * returns its length, or a negative attn_status for a bad id. */
+/* Writes the NUL-terminated name of instance `id` (kernel family and template parameters, e.g.
+ * "prefill_bf16_ring d128 qb1 w8 hpw4 slots8 pf5 seqmajor" or "decode_bf16_balanced d128 w4 percu1"),
+ * truncated to buf_bytes - 1 characters; returns the length written, or a negative attn_status for a bad id. */
 int attn_instance_name(int is_decode, int id, char *buf, size_t buf_bytes);
 /* Instance the next hot call with these args would launch (cache winner, else heuristic), or <0. */
 int attn_selected_instance(const attn_args *args, int is_decode);
 /* Force an instance id for all later hot calls of that kind (-1 = back to automatic).  Invalid
  * combinations are rejected by the hot call with ATTN_ERR_UNSUPPORTED. */
 void attn_force_instance(int is_decode, int id);
-
-/*
- * Measurement aids (not part of the paper's method): what the device sustains for the two resources
- * that bound the path, for quoting a result against the achievable next to the published peak.
- * attn_probe_hbm_read enqueues a streaming read of `bytes` bytes (16-byte aligned device buffer,
- * at least 16 bytes); `sink4` is a 4-byte device word that the kernel may touch.  attn_probe_mfma_bf16
- * enqueues `iters` rounds of four independent 32x32x16 bf16 MFMAs on eight wavefronts per compute
- * unit and returns the number of floating-point operations enqueued (> 0), or a negative attn_status.
- * The caller times them on its stream.
- */
-int attn_probe_hbm_read(const void *buf, size_t bytes, void *sink4, void *hip_stream);
-int64_t attn_probe_mfma_bf16(int iters, void *sink4, void *hip_stream);
 
 const char *attn_status_string(int status);
 

@@ -24,7 +24,6 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     make_args,
-    probe_achievable,
     KvWriteArgs,
     attn_kv_cache_write,
     make_kv_write_args,

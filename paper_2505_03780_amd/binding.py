@@ -65,14 +65,6 @@ def library_path() -> str:
     return _LIB_PATH
 
 
-def use_library(path: str) -> None:
-    """Load another build of the library (the profiling build) instead; only before the first load."""
-    global _LIB_PATH
-    if _lib is not None:
-        raise RuntimeError("the library is already loaded")
-    _LIB_PATH = path
-
-
 def load_library():
     """Load the HIP library.  Raises if it has not been built (python -m paper_2505_03780_amd.build)."""
     global _lib
@@ -106,10 +98,6 @@ def load_library():
     lib.attn_force_instance.argtypes = [ctypes.c_int, ctypes.c_int]
     lib.attn_status_string.restype = ctypes.c_char_p
     lib.attn_status_string.argtypes = [ctypes.c_int]
-    lib.attn_probe_hbm_read.restype = ctypes.c_int
-    lib.attn_probe_hbm_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
-    lib.attn_probe_mfma_bf16.restype = ctypes.c_int64
-    lib.attn_probe_mfma_bf16.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
     lib.attn_kv_cache_write.restype = ctypes.c_int
     lib.attn_kv_cache_write.argtypes = [ctypes.POINTER(KvWriteArgs), ctypes.c_void_p]
     R = ctypes.POINTER(RmsNormArgs)
@@ -400,36 +388,3 @@ def attn_kv_cache_write(k_new, v_new, k_cache, v_cache, slot_mapping, stream=Non
     rc = load_library().attn_kv_cache_write(ctypes.byref(a), _stream_ptr(stream))
     if rc != 0:
         raise AttnError(rc, "attn_kv_cache_write")
-
-
-# ---- measurement aids ----------------------------------------------------------------------------------
-
-def probe_achievable(read_bytes: int = 1 << 31, mfma_iters: int = 1 << 14) -> dict:
-    """Times the library's two probes on the current stream: sustained HBM read bandwidth (GB/s) and
-    sustained bf16 MFMA rate (TFLOP/s)."""
-    import torch
-
-    lib = load_library()
-    buf = torch.zeros(read_bytes // 4, dtype=torch.int32, device="cuda")
-    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
-    sp = _stream_ptr(None)
-    out = {}
-    for name in ("hbm_read_GBps", "mfma_bf16_TFLOPs"):
-        best = 0.0
-        for rep in range(4):  # the first repetition warms clocks and caches
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            if name == "hbm_read_GBps":
-                rc = lib.attn_probe_hbm_read(buf.data_ptr(), read_bytes, sink.data_ptr(), sp)
-                work = float(read_bytes) / 1e9
-            else:
-                rc = lib.attn_probe_mfma_bf16(mfma_iters, sink.data_ptr(), sp)
-                work = float(rc) / 1e12
-            if rc < 0:
-                raise AttnError(int(rc), "probe")
-            e1.record()
-            torch.cuda.synchronize()
-            if rep:
-                best = max(best, work / (e0.elapsed_time(e1) * 1e-3))
-        out[name] = best
-    return out

@@ -25,6 +25,8 @@
 #include <unordered_map>
 #include <vector>
 
+#include <fcntl.h>
+#include <sys/file.h>
 #include <unistd.h>
 
 #include "../../include/attn.h"
@@ -39,7 +41,10 @@ constexpr const char *kCacheMagic = "attn-tune-cache-v1";
 // Identifies the set of compiled instances: a cache line tuned against another set must not be
 // trusted (the paper asks that cached results record the environment they were measured in).
 std::string build_id();
-constexpr int kMinSplitLen = 128;
+// Bounds on the split-K records of the fixed-split decode kernels: a context is cut into at most
+// kMaxPartsPerSeq parts, and a batch into at most two parts per compute unit in all (more parts add
+// workspace traffic and merge work, never parallelism: every part already is Hkv workgroups).
+constexpr int kMaxPartsPerSeq = 64;
 
 std::mutex g_mu;
 std::unordered_map<std::string, int> g_winner[2];  // [is_decode]: bucket key -> instance id
@@ -168,7 +173,7 @@ std::vector<std::string> neighbour_keys(const KParams &p, int dtype, int is_deco
     return out;
 }
 
-constexpr int kMaxBalancedWgs = 2048;  // workspace bound for the token-balanced decode
+constexpr int kMaxBalancedWgs = 2048;  // launch bound of the token-balanced decode
 
 int compute_units()
 {
@@ -183,6 +188,25 @@ int compute_units()
     }
     cached.store(prop.multiProcessorCount);
     return prop.multiProcessorCount;
+}
+
+// Parts per sequence a fixed-split decode instance cuts the longest context into (1: no split).
+int fixed_parts(const KParams &p, const Instance &inst)
+{
+    const int sl = inst.split_len;
+    return (sl <= 0 || sl >= p.max_kv_len) ? 1 : (p.max_kv_len + sl - 1) / sl;
+}
+
+// The parameter-dependency predicate of an instance (the paper's requirement list asks for
+// configuration spaces that carry the dependencies between parameters): the kernel's own conditions,
+// and for a fixed-split decode instance the bound on the split-K records.
+bool usable(const Instance &inst, const KParams &p, int is_decode)
+{
+    if (!inst.valid(p)) return false;
+    if (!is_decode || inst.split_len <= 0) return true;
+    const int parts = fixed_parts(p, inst);
+    if (parts == 1) return true;
+    return parts <= kMaxPartsPerSeq && (int64_t)p.num_seqs * parts <= std::max<int64_t>(2 * compute_units(), 2);
 }
 
 void apply_split(KParams &p, const Instance &inst)
@@ -212,7 +236,7 @@ int find_instance(int is_decode, const KParams &p, int waves, int hpw, int bn, i
     int n;
     const Instance *t = instances(is_decode, &n);
     for (int i = 0; i < n; ++i) {
-        if (!t[i].valid(p)) continue;
+        if (!usable(t[i], p, is_decode)) continue;
         if (t[i].waves == waves && t[i].heads_per_wg == hpw && t[i].block_n == bn && (bm <= 0 || t[i].block_m == bm) &&
             t[i].split_len == split_len && t[i].variant == variant && (stages <= 0 || t[i].stages == stages))
             return i;
@@ -269,6 +293,9 @@ int heuristic(const KParams &p, int is_decode)
                 sl *= 2;
                 wide = true;
             }
+            // and the batch at most two parts per compute unit in all (the bound `usable` enforces)
+            while (sl > 0 && sl < 4096 && (int64_t)p.num_seqs * ((p.max_kv_len + sl - 1) / sl) > 2 * compute_units()) sl *= 2;
+            if (sl >= p.max_kv_len || (sl > 0 && (int64_t)p.num_seqs * ((p.max_kv_len + sl - 1) / sl) > 2 * compute_units())) sl = 0;
             if (wide) id = find_instance(1, p, 8, 16, 32, 0, sl);
             if (id < 0) id = find_instance(1, p, 4, 16, 32, 0, sl);
             if (id < 0) id = find_instance(1, p, 4, 16, 32, 0, 0);
@@ -278,7 +305,7 @@ int heuristic(const KParams &p, int is_decode)
     }
     if (id >= 0) return id;
     for (int i = 0; i < n; ++i)
-        if (t[i].valid(p)) return i;
+        if (usable(t[i], p, is_decode)) return i;
     return -1;
 }
 
@@ -347,8 +374,12 @@ bool parse_line(const std::string &line, CacheLine *out)
     return true;
 }
 
-int read_cache_file(const char *path, std::vector<CacheLine> *lines)
+// Reads the lines of a cache file.  A line that does not parse is skipped and counted, never a reason
+// to drop the lines after it (they may be other environments' winners).  ATTN_ERR_CACHE_IO for a file
+// that is missing or does not start with the magic line.
+int read_cache_file(const char *path, std::vector<CacheLine> *lines, int *damaged)
 {
+    *damaged = 0;
     std::ifstream in(path);
     if (!in) return ATTN_ERR_CACHE_IO;
     std::string line;
@@ -356,7 +387,10 @@ int read_cache_file(const char *path, std::vector<CacheLine> *lines)
     while (std::getline(in, line)) {
         if (line.empty() || line[0] == '#') continue;
         CacheLine cl;
-        if (!parse_line(line, &cl)) return ATTN_ERR_CACHE_IO;
+        if (!parse_line(line, &cl)) {
+            ++*damaged;
+            continue;
+        }
         lines->push_back(cl);
     }
     return ATTN_OK;
@@ -365,8 +399,10 @@ int read_cache_file(const char *path, std::vector<CacheLine> *lines)
 int load_cache_locked(const char *path)
 {
     std::vector<CacheLine> lines;
-    int rc = read_cache_file(path, &lines);
+    int damaged = 0;
+    int rc = read_cache_file(path, &lines, &damaged);
     if (rc != ATTN_OK) return rc;
+    if (lines.empty() && damaged > 0) return ATTN_ERR_CACHE_IO;  // nothing but damage
     const std::string env = env_key_impl();
     for (const CacheLine &cl : lines) {
         if (cl.env != env) continue;  // measured on another device or library build
@@ -413,10 +449,11 @@ struct SelectMemo {
 // ATTN_FORCE_INSTANCE=<exact instance name>: calls of the kind that has an instance of that name use
 // it whenever it is valid for the shape (and fall back to the usual choice when it is not), as if
 // it were every bucket's winner.  ATTN_LOG=1: one line on stderr whenever a shape is resolved.
-// Both are read once.
+// ATTN_DEBUG_VALIDATE=1: hot calls check the device-side integers first.  All are read once.
 struct EnvKnobs {
     int forced[2] = {-1, -1};
     bool log = false;
+    bool debug_validate = false;
 };
 
 const EnvKnobs &env_knobs()
@@ -425,6 +462,8 @@ const EnvKnobs &env_knobs()
         EnvKnobs e;
         const char *lg = getenv("ATTN_LOG");
         e.log = lg && lg[0] == '1';
+        const char *dbg = getenv("ATTN_DEBUG_VALIDATE");
+        e.debug_validate = dbg && dbg[0] == '1';
         if (const char *name = getenv("ATTN_FORCE_INSTANCE"))
             for (int d = 0; d < 2; ++d) e.forced[d] = instance_by_name(d, name);
         return e;
@@ -441,14 +480,14 @@ int select_instance_slow(const KParams &p, int dtype, int is_decode)
     const std::string key = bucket_key(p, dtype, is_decode);
     int id = -1;
     const char *why = "heuristic";
-    if (env.forced[is_decode] >= 0 && t[env.forced[is_decode]].valid(p)) {
+    if (env.forced[is_decode] >= 0 && usable(t[env.forced[is_decode]], p, is_decode)) {
         id = env.forced[is_decode];
         why = "ATTN_FORCE_INSTANCE";
     }
     if (id < 0) {
         std::lock_guard<std::mutex> lk(g_mu);
         auto it = g_winner[is_decode].find(key);
-        if (it != g_winner[is_decode].end() && it->second < n && t[it->second].valid(p)) {
+        if (it != g_winner[is_decode].end() && it->second < n && usable(t[it->second], p, is_decode)) {
             id = it->second;
             why = "tuned";
         }
@@ -469,7 +508,7 @@ int select_instance(const KParams &p, int dtype, int is_decode)
     if (forced >= 0) {
         int n;
         const Instance *t = instances(is_decode, &n);
-        return forced < n && t[forced].valid(p) ? forced : ATTN_ERR_UNSUPPORTED;
+        return forced < n && usable(t[forced], p, is_decode) ? forced : ATTN_ERR_UNSUPPORTED;
     }
     static thread_local SelectMemo memo[2];
     SelectMemo &m = memo[is_decode];
@@ -492,13 +531,26 @@ size_t balanced_workspace_bytes(int num_seqs, int num_q_heads, int head_dim, int
     return (size_t)(wgs + num_seqs) * num_q_heads * partial_stride(head_dim) * sizeof(float) + (size_t)(num_seqs + 1) * sizeof(int32_t);
 }
 
-size_t decode_workspace_bytes(int num_seqs, int num_q_heads, int head_dim, int max_kv_len)
+// Workspace bytes instance `inst` needs for the call `p` (0: it writes the output directly).
+size_t instance_workspace_bytes(const Instance &inst, const KParams &p_in)
 {
-    // sized for the shortest part any fixed-split instance uses and for the largest token-balanced
-    // launch, so every instance fits
-    const int64_t splits = std::max<int64_t>(1, (max_kv_len + kMinSplitLen - 1) / kMinSplitLen);
-    const size_t fixed = (size_t)num_seqs * num_q_heads * splits * partial_stride(head_dim) * sizeof(float);
-    return std::max(fixed, balanced_workspace_bytes(num_seqs, num_q_heads, head_dim, kMaxBalancedWgs));
+    KParams p = p_in;
+    apply_split(p, inst);
+    if (inst.split_len < 0) return balanced_workspace_bytes(p.num_seqs, p.num_q_heads, p.head_dim, p.num_splits);
+    if (p.num_splits <= 1) return 0;
+    return (size_t)p.num_seqs * p.num_q_heads * p.num_splits * partial_stride(p.head_dim) * sizeof(float);
+}
+
+// The largest need of any instance that may be chosen for this call (cache winner, forced or built-in),
+// so the answer does not depend on the state of the winner cache.
+size_t decode_workspace_bytes(const KParams &p)
+{
+    int n;
+    const Instance *t = instances(1, &n);
+    size_t need = 0;
+    for (int i = 0; i < n; ++i)
+        if (usable(t[i], p, 1)) need = std::max(need, instance_workspace_bytes(t[i], p));
+    return need;
 }
 
 // Debug aid, switched on by ATTN_DEBUG_VALIDATE=1 in the environment: the device-side integers that
@@ -546,8 +598,7 @@ int run(const attn_args *a, int is_decode, hipStream_t stream, int instance_over
     int rc = validate(a, is_decode);
     if (rc != ATTN_OK) return rc;
     if (a->num_seqs == 0 || a->total_q == 0) return ATTN_OK;
-    const char *dbg = getenv("ATTN_DEBUG_VALIDATE");
-    if (dbg && dbg[0] == '1') {
+    if (env_knobs().debug_validate) {
         rc = debug_validate_device_side(a, is_decode, stream);
         if (rc != ATTN_OK) {
             (void)hipGetLastError();
@@ -562,14 +613,13 @@ int run(const attn_args *a, int is_decode, hipStream_t stream, int instance_over
     const Instance *t = instances(is_decode, &n);
     int id = instance_override >= 0 ? instance_override : select_instance(p, a->dtype, is_decode);
     if (id < 0) return id;
-    if (id >= n || !t[id].valid(p)) return ATTN_ERR_UNSUPPORTED;
+    if (id >= n || !usable(t[id], p, is_decode)) return ATTN_ERR_UNSUPPORTED;
     if (is_decode) {
+        const size_t need = instance_workspace_bytes(t[id], p);
         apply_split(p, t[id]);
-        const bool balanced = t[id].split_len < 0;
-        if (balanced || p.num_splits > 1) {
-            const size_t need = balanced ? balanced_workspace_bytes(p.num_seqs, p.num_q_heads, p.head_dim, p.num_splits)
-                                         : (size_t)p.num_seqs * p.num_q_heads * p.num_splits * partial_stride(p.head_dim) * sizeof(float);
+        if (need > 0) {
             if (!a->workspace || a->workspace_bytes < need) return ATTN_ERR_WORKSPACE;
+            if ((uintptr_t)a->workspace & 7) return ATTN_ERR_WORKSPACE;  // records are accessed as 8-byte pairs
         }
     }
     if (t[id].launch(p, stream) != hipSuccess) return ATTN_ERR_HIP;
@@ -683,11 +733,10 @@ int tune(const attn_args *shape, int is_decode, const char *cache_path, int iter
     const size_t q_elems = (size_t)total_q * Hq * D;
     const size_t kv_elems = paged ? (size_t)nblocks * bs * Hkv * D : (size_t)total_kv * Hkv * D;
     DeviceBuf dq, dout, dk, dv, dtab, dqsl, dkvsl, dlens, dws;
-    const size_t ws_bytes = is_decode ? decode_workspace_bytes(B, Hq, D, max_kv) : 0;
     if (dq.alloc(q_elems * 2) != hipSuccess || dout.alloc(q_elems * 2) != hipSuccess || dk.alloc(kv_elems * 2) != hipSuccess ||
         dv.alloc(kv_elems * 2) != hipSuccess || dtab.alloc(table.size() * 4) != hipSuccess ||
         dqsl.alloc((B + 1) * 4) != hipSuccess || dkvsl.alloc((B + 1) * 4) != hipSuccess || dlens.alloc(B * 4) != hipSuccess ||
-        dws.alloc(ws_bytes) != hipSuccess) {
+        false) {
         (void)hipGetLastError();
         return ATTN_ERR_HIP;
     }
@@ -727,18 +776,34 @@ int tune(const attn_args *shape, int is_decode, const char *cache_path, int iter
     a.kv_start_loc = paged ? nullptr : (const int32_t *)dkvsl.p;
     a.seq_lens = (const int32_t *)dlens.p;
     if (a.scale == 0.f) a.scale = 1.f / std::sqrt((float)D);
-    a.workspace = dws.p;
-    a.workspace_bytes = ws_bytes;
 
     int rc = validate(&a, is_decode);
     if (rc != ATTN_OK) return rc;
+    const size_t ws_bytes = is_decode ? decode_workspace_bytes(to_kparams(&a, is_decode)) : 0;
+    if (dws.alloc(ws_bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return ATTN_ERR_HIP;
+    }
+    a.workspace = dws.p;
+    a.workspace_bytes = ws_bytes;
     const KParams p = to_kparams(&a, is_decode);
     const std::string key = bucket_key(p, a.dtype, is_decode);
 
     int n;
     const Instance *t = instances(is_decode, &n);
-    hipEvent_t e0, e1;
-    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return ATTN_ERR_HIP;
+    struct Events {  // destroyed on every way out of this function
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        ~Events()
+        {
+            if (e0) (void)hipEventDestroy(e0);
+            if (e1) (void)hipEventDestroy(e1);
+        }
+    } ev;
+    if (hipEventCreate(&ev.e0) != hipSuccess || hipEventCreate(&ev.e1) != hipSuccess) {
+        (void)hipGetLastError();
+        return ATTN_ERR_HIP;
+    }
+    const hipEvent_t e0 = ev.e0, e1 = ev.e1;
     // median of `count` timed launches after `warm` untimed ones; < 0 if the instance fails.  A launch
     // slower than `give_up_us` ends the measurement early (the instance cannot win any more).
     auto time_instance = [&](int id, int warm, int count, double give_up_us) -> double {
@@ -771,7 +836,7 @@ int tune(const attn_args *shape, int is_decode, const char *cache_path, int iter
     };
     std::vector<Cand> cand;
     for (int id = 0; id < n; ++id)
-        if (t[id].valid(p)) cand.push_back(Cand{id, 0.0, false});
+        if (usable(t[id], p, is_decode)) cand.push_back(Cand{id, 0.0, false});
     if (cand.empty()) return ATTN_ERR_UNSUPPORTED;
     // seeds always survive the first cut: the built-in choice and the winners of the neighbouring buckets
     {
@@ -827,8 +892,6 @@ int tune(const attn_args *shape, int is_decode, const char *cache_path, int iter
             }
     }
     if (flags & 1) fprintf(stderr, "[attn_tune] %s :: %d launches in all\n", key.c_str(), launches);
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
     if (best < 0) return ATTN_ERR_UNSUPPORTED;
     {
         std::lock_guard<std::mutex> lk(g_mu);
@@ -847,27 +910,56 @@ std::string environment_key() { return env_key_impl(); }
 
 int merge_cache_line(const char *path, const std::string &key, const std::string &instance_name, double us)
 {
-    // keep every other line, replace this (environment, bucket) pair
-    std::vector<CacheLine> lines;
-    (void)read_cache_file(path, &lines);  // a missing or damaged file is simply rewritten
-    const std::string env = env_key_impl();
-    std::vector<CacheLine> keep;
-    for (const CacheLine &cl : lines)
-        if (!(cl.env == env && cl.key == key)) keep.push_back(cl);
-    keep.push_back(CacheLine{env, key, instance_name, us});
-    const std::string tmp = std::string(path) + ".tmp." + std::to_string((long)getpid());
-    {
-        std::ofstream out(tmp, std::ios::trunc);
-        if (!out) return ATTN_ERR_CACHE_IO;
-        out << kCacheMagic << "\n";
-        for (const CacheLine &cl : keep) out << cl.env << "\t" << cl.key << "\t" << cl.inst << "\t" << cl.us << "\n";
-        out.flush();
-        if (!out) {
-            (void)remove(tmp.c_str());
-            return ATTN_ERR_CACHE_IO;
+    // Read, change and replace under an exclusive lock on a side file, so that two processes tuning into
+    // one cache file do not lose each other's lines (the data file itself is replaced by rename and
+    // cannot carry the lock).
+    struct Lock {
+        int fd = -1;
+        explicit Lock(const std::string &p)
+        {
+            fd = open(p.c_str(), O_CREAT | O_RDWR | O_CLOEXEC, 0644);
+            if (fd >= 0 && flock(fd, LOCK_EX) != 0) {
+                close(fd);
+                fd = -1;
+            }
         }
+        ~Lock()
+        {
+            if (fd >= 0) {
+                (void)flock(fd, LOCK_UN);
+                close(fd);
+            }
+        }
+    } lock(std::string(path) + ".lock");
+    if (lock.fd < 0) return ATTN_ERR_CACHE_IO;
+
+    // keep every other line, replace this (environment, bucket) pair; damaged lines are dropped, a
+    // missing file or one without the magic line starts afresh
+    std::vector<CacheLine> lines;
+    int damaged = 0;
+    (void)read_cache_file(path, &lines, &damaged);
+    const std::string env = env_key_impl();
+    std::ostringstream text;
+    text << kCacheMagic << "\n";
+    for (const CacheLine &cl : lines)
+        if (!(cl.env == env && cl.key == key)) text << cl.env << "\t" << cl.key << "\t" << cl.inst << "\t" << cl.us << "\n";
+    text << env << "\t" << key << "\t" << instance_name << "\t" << us << "\n";
+    const std::string body = text.str();
+
+    const std::string tmp = std::string(path) + ".tmp." + std::to_string((long)getpid());
+    const int fd = open(tmp.c_str(), O_CREAT | O_TRUNC | O_WRONLY | O_CLOEXEC, 0644);
+    if (fd < 0) return ATTN_ERR_CACHE_IO;
+    bool ok = true;
+    for (size_t done = 0; ok && done < body.size();) {
+        const ssize_t w = write(fd, body.data() + done, body.size() - done);
+        if (w <= 0)
+            ok = false;
+        else
+            done += (size_t)w;
     }
-    if (rename(tmp.c_str(), path) != 0) {
+    ok = ok && fsync(fd) == 0;  // the new contents are on disk before the name points at them
+    ok = (close(fd) == 0) && ok;
+    if (!ok || rename(tmp.c_str(), path) != 0) {
         (void)remove(tmp.c_str());
         return ATTN_ERR_CACHE_IO;
     }
@@ -940,8 +1032,18 @@ int attn_decode_paged(const attn_args *args, void *hip_stream) { return run(args
 size_t attn_workspace_bytes(const attn_args *a, int is_decode)
 {
     if (!a || a->struct_bytes != sizeof(attn_args) || !is_decode) return 0;
-    if (a->num_seqs <= 0 || a->num_q_heads <= 0 || a->max_kv_len < 0 || (a->head_dim != 64 && a->head_dim != 128)) return 0;
-    return decode_workspace_bytes(a->num_seqs, a->num_q_heads, a->head_dim, a->max_kv_len);
+    if (a->num_seqs <= 0 || a->num_q_heads <= 0 || a->num_kv_heads <= 0 || a->num_q_heads % a->num_kv_heads || a->max_kv_len < 0 ||
+        (a->head_dim != 64 && a->head_dim != 128) || !is16(a->dtype))
+        return 0;
+    KParams p = to_kparams(a, 1);
+    // pointer fields are ignored: decode is always paged, whatever block_table holds at this point
+    static const int32_t dummy_table = 0;
+    p.block_table = &dummy_table;
+    if (p.block_size <= 0) {
+        p.block_size = a->block_size > 0 ? a->block_size : 16;
+        p.block_shift = ilog2_ceil(p.block_size);
+    }
+    return decode_workspace_bytes(p);
 }
 
 int attn_tune(const attn_args *shape_like, int is_decode, const char *cache_path, int iters, int flags)

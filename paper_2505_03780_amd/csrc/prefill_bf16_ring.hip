@@ -135,13 +135,6 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
     constexpr int KSTEPS = kHD / 16;
     constexpr int DB = kHD / 32;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-#ifdef ATTN_RING_PROFILE
-    // Profiling build only: per-wavefront time stamps (100 MHz wall clock) and where the wave ran, written
-    // to the workspace as 16 words per wave: [0..4] cycles per loop phase, [5] units, [6] loop cycles,
-    // [7] clock at the end of the loop, [8] at entry, [9] at the start of the loop, [10] at exit,
-    // [11] block index, [12] hardware id register, [13] XCD id.
-    const unsigned long long prof_entry = wall_clock64();
-#endif
 
     // ---- which (head group, sequence, query tile) ---------------------------------------------
     // Workgroups go to the eight XCDs round-robin, so with the KV head innermost every XCD (and its
@@ -225,7 +218,7 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
     const int n_units = (kv_end + kUnit - 1) / kUnit;
 
     elem *obase = (elem *)p.out;
-    if (n_units == 0) {  // no visible key at all (non-causal call on an empty context): zeros
+    if (n_units <= 0) {  // no visible key at all (an empty context; also lengths that break seq_lens >= n_q): zeros
         for (int i = lane; i < C::kWaveTok * (kHD / 8); i += 64) {
             const int t = t0w + i / (kHD / 8);
             if (t < n_q)
@@ -487,19 +480,6 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
     // Invariant at the top of iteration u: S(u) settled in `cur`; kf = K(u+1); units <= u+2 resident;
     // units <= u+PF-1 issued.  S(u+1) is computed even past the last unit (its ring slot then holds the
     // re-read rows of a dummy transfer and every entry is masked): no branch inside the iteration.
-#ifdef ATTN_RING_PROFILE
-    unsigned long long prof_t[5] = {0, 0, 0, 0, 0}, prof_last = __builtin_readcyclecounter();
-    const unsigned long long prof_begin = prof_last;
-    const unsigned long long prof_loop_begin = wall_clock64();
-#define PROF_MARK(i)                                                   \
-    {                                                                  \
-        const unsigned long long now = __builtin_readcyclecounter();   \
-        prof_t[i] += now - prof_last;                                  \
-        prof_last = now;                                               \
-    }
-#else
-#define PROF_MARK(i)
-#endif
     auto iteration = [&](int u, f32x16 (&cur)[QB], f32x16 (&nxt)[QB], auto cur_tag, auto nxt_tag) {
         constexpr bool CUR_MASK = decltype(cur_tag)::value;
         constexpr bool NXT_MASK = decltype(nxt_tag)::value;
@@ -544,7 +524,6 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
             if (g == 1) transpose_load(u + 1, raw);  // this wave's share of V(u+1), stored late in phase Y
             __builtin_amdgcn_sched_barrier(0);
         }
-        PROF_MARK(0)
 
         float mx[QB];
         int rel[QB];
@@ -579,7 +558,6 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
         }
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) l_run[qb] += sum[qb];
-        PROF_MARK(1)
         float bm[QB];
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
@@ -587,13 +565,7 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
             bm[qb] = NXT_MASK ? m : m * c;
         }
         move_reference(bm);
-        PROF_MARK(2)
-#ifdef ATTN_RING_PROFILE
-        wait_vmcnt<2 * NDMA * (PF - 3)>();
-        PROF_MARK(3)
-#endif
         ring_barrier();
-        PROF_MARK(4)
     };
     auto copy_back = [&]() {
 #pragma unroll
@@ -621,17 +593,6 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
     }
     if (u < n_units) iteration(u, s_cur, s_nxt, Masked{}, Masked{});
 
-#ifdef ATTN_RING_PROFILE
-    if (lane == 0 && p.workspace) {
-        unsigned long long *dst = (unsigned long long *)p.workspace + ((size_t)blockIdx.x * WAVES + wave) * 16;
-        for (int i = 0; i < 5; ++i) dst[i] = prof_t[i];
-        dst[5] = n_units;
-        dst[6] = __builtin_readcyclecounter() - prof_begin;
-        dst[7] = wall_clock64();
-        dst[8] = prof_entry;
-        dst[9] = prof_loop_begin;
-    }
-#endif
     // ---- epilogue: O / l, transposed through LDS, whole rows to HBM ------------------------------
     wait_vmcnt<0>();
     __syncthreads();  // the ring is free: every wave is past its last V read and no DMA is in flight
@@ -668,19 +629,6 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
         if (t < n_q)
             *(u32x4 *)(obase + (int64_t)(q0 + t) * p.o_stride_tok + (int64_t)head * p.o_stride_head + 8 * chunk) = row;
     }
-#ifdef ATTN_RING_PROFILE
-    wait_vmcnt<0>();
-    if (lane == 0 && p.workspace) {
-        unsigned long long *dst = (unsigned long long *)p.workspace + ((size_t)blockIdx.x * WAVES + wave) * 16;
-        unsigned hw_id, xcc_id;
-        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw_id));
-        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc_id));
-        dst[10] = wall_clock64();
-        dst[11] = blockIdx.x;
-        dst[12] = hw_id;
-        dst[13] = xcc_id;
-    }
-#endif
 }
 
 template <typename E, int QB, int HPW, int NSLOT, int PF, int WAVES>

@@ -1,11 +1,12 @@
-// Measurement aids: what this machine actually sustains for the two resources the attention path is
-// bounded by, so that a benchmark can quote its figures against the published peaks and against
-// these.  Not part of the method: a streaming read of a buffer (HBM) and a loop of independent
-// 32x32x16 bf16 MFMAs (matrix pipe).
+// Measurement aids for the benchmark, built into a small library of their own (libprobe_gfx950.so;
+// not part of the attention library or its ABI): what this machine actually sustains for the two
+// resources the attention path is bounded by, so that a result can be quoted against the published
+// peaks and against these.  A streaming read of a buffer (HBM) and a loop of independent 32x32x16
+// bf16 MFMAs (matrix pipe).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "../../include/attn.h"
+#include "probe.h"
 
 namespace attn {
 namespace {
@@ -73,31 +74,31 @@ __global__ __launch_bounds__(512) void mfma_bf16_kernel(int iters, float *sink)
 }  // namespace
 }  // namespace attn
 
-extern "C" int attn_probe_hbm_read(const void *buf, size_t bytes, void *sink4, void *hip_stream)
+extern "C" int probe_hbm_read(const void *buf, size_t bytes, void *sink4, void *hip_stream)
 {
     using namespace attn;
-    if (!buf || !sink4) return ATTN_ERR_NULL;
-    if (bytes < 16 || ((uintptr_t)buf & 15) || ((uintptr_t)sink4 & 3)) return ATTN_ERR_SHAPE;
+    if (!buf || !sink4) return -1;
+    if (bytes < 16 || ((uintptr_t)buf & 15) || ((uintptr_t)sink4 & 3)) return -2;
     const size_t n_vec = bytes / 16;
     int dev = 0, cus = 256;
     hipDeviceProp_t prop;
     if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) cus = prop.multiProcessorCount;
     (void)hipGetLastError();
     hipLaunchKernelGGL(hbm_read_kernel, dim3((unsigned)(cus * 4)), dim3(256), 0, (hipStream_t)hip_stream, (const u32x4 *)buf, n_vec, (uint32_t *)sink4);
-    return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_ERR_HIP;
+    return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 
-extern "C" int64_t attn_probe_mfma_bf16(int iters, void *sink4, void *hip_stream)
+extern "C" int64_t probe_mfma_bf16(int iters, void *sink4, void *hip_stream)
 {
     using namespace attn;
-    if (!sink4) return ATTN_ERR_NULL;
-    if (iters <= 0 || iters > (1 << 24)) return ATTN_ERR_SHAPE;
+    if (!sink4) return -1;
+    if (iters <= 0 || iters > (1 << 24)) return -2;
     int dev = 0, cus = 256;
     hipDeviceProp_t prop;
     if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) cus = prop.multiProcessorCount;
     (void)hipGetLastError();
     // one workgroup of eight wavefronts per compute unit: two wavefronts per SIMD
     hipLaunchKernelGGL(mfma_bf16_kernel, dim3((unsigned)cus), dim3(512), 0, (hipStream_t)hip_stream, iters, (float *)sink4);
-    if (hipGetLastError() != hipSuccess) return ATTN_ERR_HIP;
+    if (hipGetLastError() != hipSuccess) return -6;
     return (int64_t)cus * 8 * (int64_t)iters * 4 * 32768;  // floating-point operations enqueued
 }

@@ -104,20 +104,24 @@ def check_full(wl: W.Workload, is_decode=None, what=""):
 
 
 def sample_rows(wl: W.Workload, n: int, seed: int = 0):
-    """Random (sequence, token, head) triples, always including each sequence's first and last token."""
+    """Up to n distinct random (sequence, token, head) triples (drawn without replacement), always
+    including each sequence's first and last token."""
     rng = np.random.default_rng(seed)
     nq = wl.q_lens()
-    seqs, toks, heads = [], [], []
+    H = wl.num_q_heads
+    qsl = wl.query_start_loc.astype(np.int64)
+    total = int(qsl[-1]) * H
+    picked = []
     for s in range(wl.num_seqs):
         if nq[s] == 0:
             continue
         for t in {0, int(nq[s]) - 1}:
-            seqs.append(s); toks.append(t); heads.append(int(rng.integers(wl.num_q_heads)))
-    live = np.nonzero(nq > 0)[0]
-    while len(seqs) < n and live.size:
-        s = int(rng.choice(live))
-        seqs.append(s); toks.append(int(rng.integers(nq[s]))); heads.append(int(rng.integers(wl.num_q_heads)))
-    return np.array(seqs, np.int32), np.array(toks, np.int32), np.array(heads, np.int32)
+            picked.append((int(qsl[s]) + t) * H + int(rng.integers(H)))
+    rest = rng.permutation(total)[: max(0, min(n, total) - len(picked))]
+    flat = np.unique(np.concatenate([np.asarray(picked, np.int64), rest.astype(np.int64)]))
+    row, heads = flat // H, flat % H
+    seqs = np.searchsorted(qsl, row, side="right") - 1
+    return seqs.astype(np.int32), (row - qsl[seqs]).astype(np.int32), heads.astype(np.int32)
 
 
 def check_sampled(wl: W.Workload, n_rows: int, is_decode=None, what="", seed=0, dw=None):

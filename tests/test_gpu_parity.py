@@ -5,7 +5,7 @@ import torch
 
 import paper_2505_03780_amd as A
 import workloads as W
-from attn_testlib import DeviceWorkload, assert_close, check_full, check_sampled, oracle_problem, to_host_f64
+from attn_testlib import DeviceWorkload, assert_close, check_full, oracle_problem, to_host_f64
 
 import oracle
 
@@ -39,12 +39,40 @@ def test_config1_tiny_fp32_full():
     check_full(W.config1())
 
 
+def _paged_f32(seed, q_lens, kv_lens, Hq, Hkv, D, bs):
+    """A paged fp32 workload: packed fp32 K/V scattered into a pool by a random block table (a pure
+    copy); blocks and slots that no sequence owns hold NaN, so a read of them would show."""
+    rng = np.random.default_rng(seed)
+    kv_lens = np.asarray(kv_lens, np.int32)
+    q_lens = np.asarray(q_lens, np.int32)
+    qsl = np.concatenate([[0], np.cumsum(q_lens)]).astype(np.int32)
+    kvsl = np.concatenate([[0], np.cumsum(kv_lens)]).astype(np.int32)
+    q = rng.standard_normal((int(qsl[-1]), Hq, D), dtype=np.float32)
+    k = rng.standard_normal((int(kvsl[-1]), Hkv, D), dtype=np.float32)
+    v = rng.standard_normal((int(kvsl[-1]), Hkv, D), dtype=np.float32)
+    nb = int(np.sum((kv_lens + bs - 1) // bs)) + 3
+    table = W._block_table(rng, kv_lens, bs, nb, int((kv_lens.max() + bs - 1) // bs) + 1)
+    kp, vp = W.scatter_to_pool(k, v, kvsl, kv_lens, table, bs, nb, fill=np.float32("nan"))
+    scale = float(np.float32(1.0 / np.sqrt(np.float32(D))))
+    paged = W.Workload("paged_f32", "prefill", "f32", q, kp, vp, qsl, kv_lens.copy(), scale, True, block_table=table, block_size=bs)
+    contig = W.Workload("contig_f32", "prefill", "f32", q, k, v, qsl, kv_lens.copy(), scale, True, kv_start_loc=kvsl)
+    return paged, contig
+
+
 @pytest.mark.parametrize("D", [64, 128])
 def test_fp32_varlen_gqa_and_paged(D):
     wl = W.make_prefill_contiguous(11, [1, 5, 64, 65, 130], 4, 2, D, dtype="f32")
     check_full(wl)
     wl = W.make_prefill_contiguous(12, [7, 70], 2, 2, D, dtype="f32", causal=False)
     check_full(wl)
+    # the fp32 kernel's block-table branch: chunked prefill over a paged prefix, block sizes 16 and 32;
+    # the same tokens in the contiguous layout give the same bits (same kernel, same summation order)
+    for bs in (16, 32):
+        paged, contig = _paged_f32(13 + bs, [1, 40, 17, 33], [1, 100, 17, 65], 4, 2, D, bs)
+        check_full(paged, what="paged fp32 bs %d" % bs)
+        a = to_host_f64(DeviceWorkload(paged).run(False))
+        b = to_host_f64(DeviceWorkload(contig).run(False))
+        assert np.array_equal(a, b), "paged and contiguous fp32 outputs differ"
 
 
 @pytest.mark.parametrize("Hq,Hkv,D", [(8, 2, 128), (4, 4, 128), (4, 2, 128), (6, 2, 128), (8, 2, 64), (2, 2, 64)])
@@ -170,40 +198,80 @@ def test_decode_writes_zeros_for_contexts_without_keys():
 
 # ---- the benchmark configurations at full size ------------------------------------------------
 
-def test_config2_decode_8b_full_size():
-    print("config 2: paged decode, batch 64, ctx U[512,4096]", flush=True)
-    check_full(W.config2())
+def _tuned(dw, is_decode):
+    """Tunes the workload's bucket the way bench.py does (its own lengths, few iterations) and returns
+    the name of the instance hot calls now take."""
+    a = dw.args(is_decode)
+    A.attn_tune(a, is_decode, None, 5, 0)
+    return A.attn_instance_name(is_decode, A.attn_selected_instance(a, is_decode))
 
 
-def test_config3_prefill_8b_full_size_sampled():
-    print("config 3: varlen prefill, 8 sequences U[256,2048]", flush=True)
-    wl = W.config3()
-    check_sampled(wl, 1500, seed=3)
-    # and one whole short sequence, every row (sequence 1: 409 tokens)
-    dw = DeviceWorkload(wl)
-    out = to_host_f64(dw.run(False))
-    s = 1
-    seqs = np.repeat(s, 409 * 4)
-    toks = np.tile(np.arange(409), 4)
-    heads = np.repeat([0, 7, 18, 31], 409)
+def _check_rows(wl, dw, seqs, toks, heads, what):
+    out = dw.run()
+    assert bool(torch.isfinite(out.float()).all()), "%s: unwritten or non-finite output rows" % what
     ref = oracle.attention_rows(oracle_problem(wl), seqs, toks, heads)
-    got = out[wl.query_start_loc[s] + toks, heads]
-    assert_close(got, ref, "bf16", "config 3 sequence 1")
+    rows = torch.from_numpy(wl.query_start_loc[seqs].astype(np.int64) + toks).cuda()
+    got = to_host_f64(out[rows, torch.from_numpy(heads.astype(np.int64)).cuda()])
+    return assert_close(got, ref, wl.dtype, what)
 
 
-def test_config4_chunked_prefill_full_size_sampled():
-    print("config 4: chunked prefill over paged prefix", flush=True)
-    check_sampled(W.config4(), 600, seed=4)
+def _full_then_tuned(wl, is_decode):
+    """Every output element of the built-in choice against the oracle, then the tuner's winner (the
+    instance bench.py times) the same way."""
+    dw = DeviceWorkload(wl)
+    ref = oracle.attention(oracle_problem(wl))
+    qsl = wl.query_start_loc
+
+    def compare(what):
+        got = to_host_f64(dw.run(is_decode))
+        for s in range(wl.num_seqs):
+            assert_close(got[qsl[s]:qsl[s + 1]], ref[qsl[s]:qsl[s + 1]], wl.dtype, "%s seq %d" % (what, s))
+        print(what, "max-abs %.3e rel-RMS %.3e" % assert_close(got, ref, wl.dtype, what), flush=True)
+
+    a = dw.args(is_decode)
+    builtin = A.attn_instance_name(is_decode, A.attn_selected_instance(a, is_decode))
+    compare("%s built-in %s" % (wl.name, builtin))
+    try:
+        winner = _tuned(dw, is_decode)
+        compare("%s tuned %s" % (wl.name, winner))
+    finally:
+        A.attn_clear_cache()
+    return builtin
+
+
+def test_config2_decode_8b_full_size():
+    print("config 2: paged decode, batch 64, ctx U[512,4096], every output element", flush=True)
+    _full_then_tuned(W.config2(), True)
+
+
+def test_config3_prefill_8b_full_size():
+    print("config 3: varlen prefill, 8 sequences U[256,2048], every output element", flush=True)
+    _full_then_tuned(W.config3(), False)
+
+
+def test_config4_chunked_prefill_full_size():
+    """Config 4 is 717 GFLOP (about a minute of fp64 oracle time): every sequence is covered, with one
+    row per query head and run of 32 tokens (no query tile of any kernel escapes) plus the first and
+    last token of every sequence for every head; built-in choice and tuner's winner."""
+    print("config 4: chunked prefill over paged prefix, stratified rows of every sequence", flush=True)
+    wl = W.config4()
+    dw = DeviceWorkload(wl)
+    seqs, toks, heads = W.stratified_rows(wl, 32)
+    assert len(seqs) == 16 * (16 + 2) * 32 and set(seqs.tolist()) == set(range(16))
+    a = dw.args(False)
+    builtin = A.attn_instance_name(False, A.attn_selected_instance(a, False))
+    print("built-in", builtin, _check_rows(wl, dw, seqs, toks, heads, "config 4 built-in " + builtin), flush=True)
+    try:
+        winner = _tuned(dw, False)
+        print("tuned", winner, _check_rows(wl, dw, seqs, toks, heads, "config 4 tuned " + winner), flush=True)
+    finally:
+        A.attn_clear_cache()
 
 
 def test_config5_decode_70b_long_full_size():
-    print("config 5: long-context paged decode, split-K", flush=True)
-    wl = W.config5()
-    dw = DeviceWorkload(wl)
-    a = dw.args(True)
-    name = A.attn_instance_name(True, A.attn_selected_instance(a, True))
+    print("config 5: long-context paged decode, split-K, every output element", flush=True)
+    name = _full_then_tuned(W.config5(), True)
     assert "split0" not in name, "long contexts must take the split-K path, got " + name
-    check_sampled(wl, 16 * 64, seed=5, dw=dw)
 
 
 @pytest.mark.parametrize("B", [333, 4200])

@@ -47,13 +47,23 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layout_matches_and_workspace_bytes():
     a = _paged(total_q=4, max_q_len=1, max_kv_len=4096)
-    # the larger of: fixed splits, 4 seqs * 32 heads * ceil(4096/128) parts * (128 + 2) floats; and the
-    # token-balanced launch, (2048 workgroups + 4 seqs) * 32 heads * 130 floats + 5 chunk prefix sums
+    # The largest need of any instance that may run (256 compute units assumed without a device).
+    # Fixed splits: at most 64 parts per context and two parts per compute unit over the batch, here
+    # 4 seqs * 32 heads * ceil(4096/128) parts * (128 + 2) floats.  Token-balanced: at most two
+    # workgroups per compute unit, (512 workgroups + 4 seqs) * 32 heads * 130 floats + 5 chunk prefix sums.
     fixed = 4 * 32 * 32 * 130 * 4
-    balanced = (2048 + 4) * 32 * 130 * 4 + 5 * 4
+    balanced = (512 + 4) * 32 * 130 * 4 + 5 * 4
     assert A.attn_workspace_bytes(a, True) == max(fixed, balanced)
+    # 64 long contexts: no fixed split with at most 512 parts in all is finer than 4096 keys (8 parts each)
     long = _paged(num_seqs=64, total_q=64, max_q_len=1, max_kv_len=32768, block_table_stride=2048)
-    assert A.attn_workspace_bytes(long, True) == 64 * 32 * 256 * 130 * 4
+    assert A.attn_workspace_bytes(long, True) == max(64 * 32 * 8 * 130 * 4, (512 + 64) * 32 * 130 * 4 + 65 * 4)
+    # the two decode configurations of the benchmark: what the caller must provide stays near what runs
+    c2 = _paged(num_seqs=64, total_q=64, max_q_len=1, max_kv_len=4071, block_table_stride=256)
+    assert A.attn_workspace_bytes(c2, True) <= 10 * 1000 * 1000
+    c5 = _paged(num_seqs=16, total_q=16, max_q_len=1, max_kv_len=32672, block_table_stride=2048, num_q_heads=64)
+    assert A.attn_workspace_bytes(c5, True) <= 20 * 1000 * 1000
+    # pointer fields are ignored
+    assert A.attn_workspace_bytes(_paged(total_q=4, max_q_len=1, max_kv_len=4096, block_table=None), True) == max(fixed, balanced)
     assert A.attn_workspace_bytes(a, False) == 0
     a.struct_bytes += 8
     assert A.attn_workspace_bytes(a, True) == 0
@@ -185,7 +195,16 @@ def test_cache_file_round_trip_stale_and_corrupt(tmp_path):
     bad.write_text("garbage\n")
     assert A.attn_load_cache(str(bad)) == -7
     bad.write_text("attn-tune-cache-v1\nonly\ttwo\n")
-    assert A.attn_load_cache(str(bad)) == -7
+    assert A.attn_load_cache(str(bad)) == -7  # nothing but damage
+    # one damaged line in the middle: the lines around it still count
+    mixed = tmp_path / "mixed.txt"
+    key2 = "prefill|bf16|d128|hq32|hkv8|contig|bs0|c1|B2|q13|kv13"
+    mixed.write_text("attn-tune-cache-v1\n%s\t%s\t%s\t12.5\n\x00\x01garbage without tabs\n%s\t%s\t%s\t7\n" % (
+        env_here, key, names_p[other], env_here, key2, names_p[other]))
+    assert A.attn_load_cache(str(mixed)) == 0
+    assert A.attn_selected_instance(_args(), False) == other
+    assert A.attn_selected_instance(_args(max_kv_len=5000, max_q_len=5000), False) == other
+    A.attn_clear_cache()
     assert A.attn_load_cache(str(tmp_path / "missing.txt")) == -7
     assert A.attn_selected_instance(_args(), False) == default
 

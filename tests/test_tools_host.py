@@ -1,4 +1,4 @@
-"""Host tests of the analysis tools: the assembly statistics parser and the lifetime report, on hand-made samples."""
+"""Host test of the assembly statistics parser, on a hand-made sample."""
 import os
 
 from paper_2505_03780_amd import isa_stats
@@ -45,30 +45,3 @@ def test_parse_counts_instructions_and_reads_the_kernel_descriptor(tmp_path):
     assert "| sample | rmsnorm_kernel<false, 64, 2, 4> | 8 | 7 | 1 | 1 | 1 | 48 (16) | 20 | 4096 | 0 |" in text
     assert "| rms norm | 1 | 8 / 8 / 8 | 7 / 7 | 7 |" in text
     assert isa_stats.family("decode_balanced_kernel<128, 8>") == "decode token-balanced"
-
-
-def test_lifetime_report_on_synthetic_stamps():
-    """The report of the profiling tool: eight waves on two shader engines of one XCD, known times."""
-    import numpy as np
-
-    from paper_2505_03780_amd import lifetime_profile as LP
-
-    t = np.zeros((8, 16), np.int64)
-    for w in range(8):
-        se = w % 2
-        units = 10 + w
-        entry = 1000 + 10 * w                       # ticks of 10 ns
-        t[w, 5] = units
-        t[w, 8] = entry
-        t[w, 9] = entry + 400                       # prologue 4 us
-        t[w, 7] = entry + 400 + 100 * units         # loop: 1 us per unit
-        t[w, 10] = t[w, 7] + 150                    # epilogue 1.5 us
-        t[w, 11] = 8 * (2 * (w // 2) + se)          # block index: XCD 0, engine = (index / 8) mod 4 = se or se + 2
-        t[w, 12] = (se << 13) | ((w // 2) << 8)     # hardware id: shader engine, compute unit
-        t[w, 13] = 0
-    text = LP.report("synthetic", "some instance", 123.4, t)
-    assert "| prologue (entry to first loop iteration) | 4.00 | 4.00 | 4.00 | 4.00 |" in text
-    assert "loop time = 0.00 us + 1.000 us per 32-key unit" in text or "loop time = -0.00 us + 1.000 us per 32-key unit" in text
-    assert "Compute units seen: 8." in text
-    rows = [l for l in text.splitlines() if l.startswith("| 0 | ")]
-    assert len(rows) == 2 and "| 4 |" in rows[0]   # two engines, four waves each

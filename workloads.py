@@ -227,6 +227,31 @@ def config5(seed=5, batch=16, lo=16384, hi=32768, num_blocks=32768):
 CONFIGS = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}
 
 
+def stratified_rows(wl: "Workload", tile: int = 32):
+    """A deterministic sample of output rows that no query tile can escape: one (sequence, token, head)
+    triple for every query head and every run of `tile` consecutive tokens of every sequence (the
+    token inside the run varies with run and head; `tile` at most the smallest query tile any kernel
+    uses), plus each sequence's first and last token for every head.  Returns int32 arrays
+    (seqs, toks, heads)."""
+    nq = wl.q_lens()
+    H = wl.num_q_heads
+    seqs, toks, heads = [], [], []
+    hh = np.arange(H, dtype=np.int64)
+    for s in range(wl.num_seqs):
+        n = int(nq[s])
+        if n == 0:
+            continue
+        for r in range((n + tile - 1) // tile):
+            t = np.minimum(r * tile + (7 * r + 3 * hh) % tile, n - 1)
+            seqs.append(np.full(H, s)); toks.append(t); heads.append(hh)
+        for t in (0, n - 1):
+            seqs.append(np.full(H, s)); toks.append(np.full(H, t)); heads.append(hh)
+    if not seqs:
+        z = np.zeros(0, np.int32)
+        return z, z.copy(), z.copy()
+    return tuple(np.concatenate(x).astype(np.int32) for x in (seqs, toks, heads))
+
+
 def scatter_to_pool(k_contig, v_contig, kv_start_loc, seq_lens, block_table, block_size, num_blocks, fill=None, seed=0):
     """Copy packed [total_kv, Hkv, D] K/V into a paged pool following block_table (a pure copy)."""
     Hkv, D = k_contig.shape[1], k_contig.shape[2]
@@ -290,3 +315,8 @@ def make_rmsnorm(seed: int, num_tokens: int, hidden: int, with_residual: bool = 
 def rmsnorm_8b_prefill(seed: int = 11) -> RmsNormWorkload:
     """8192 tokens (a prefill batch like configuration 3) x hidden 4096."""
     return make_rmsnorm(seed, 8192, 4096, True, 1e-5, "rmsnorm_8b_t8192_h4096")
+
+
+def rmsnorm_70b_prefill(seed: int = 12) -> RmsNormWorkload:
+    """8192 tokens x hidden 8192 (the 70B model's hidden size)."""
+    return make_rmsnorm(seed, 8192, 8192, True, 1e-5, "rmsnorm_70b_t8192_h8192")
