@@ -161,11 +161,23 @@ def test_graph_capture_and_replay_matches_eager():
         assert np.array_equal(eager, _bits(dw.out))
 
 
-def test_debug_validate_catches_bad_device_side_integers(monkeypatch):
+def test_debug_validate_catches_bad_device_side_integers():
+    """ATTN_DEBUG_VALIDATE is read once per process, so the checks run in a child that has it set."""
+    import os
+    import subprocess
+    import sys
+
+    here = os.path.dirname(os.path.abspath(__file__))
+    code = "import sys; sys.path[:0] = [%r, %r]; import test_gpu_invariants as T; T._debug_validate_body(); print('child ok')" % (
+        os.path.dirname(here), here)
+    r = subprocess.run([sys.executable, "-c", code], env=dict(os.environ, ATTN_DEBUG_VALIDATE="1"), capture_output=True, text=True, timeout=280)
+    assert r.returncode == 0 and "child ok" in r.stdout, (r.stdout[-1500:], r.stderr[-3000:])
+
+
+def _debug_validate_body():
     wl = W.make_paged(61, "decode", np.ones(3, np.int32), [100, 40, 257], 32, 8, 128, 16, 64)
     dw = DeviceWorkload(wl)
     lib = A.load_library()
-    monkeypatch.setenv("ATTN_DEBUG_VALIDATE", "1")
     a = dw.args(True)
     assert lib.attn_decode_paged(a, None) == 0  # consistent inputs pass
     good = int(dw.bt[1, 0])
