@@ -127,6 +127,23 @@ int attn_prefill_varlen(const attn_args *args, void *hip_stream);
 int attn_decode_paged(const attn_args *args, void *hip_stream);
 
 /*
+ * attn_decode_paged for callers that cannot provide or allocate device memory beyond the inputs and
+ * outputs: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * same kernels and the same instance choice as attn_decode_paged, but the split-K records go to a
+ * device array that the library owns (attn_static_scratch_bytes() bytes, 16 MiB, held on every GPU the
+ * library runs on until the process ends); args->workspace and args->workspace_bytes are ignored.
+ * The call allocates and frees nothing; the array's address is looked up once per device, on the
+ * first call made with that device current.  A call whose instance needs more than the array holds
+ * (very large batches: one record of (D + 2) floats per query head for every sequence and for up to
+ * four workgroups per compute unit) returns ATTN_ERR_WORKSPACE and enqueues nothing.  All calls on
+ * one GPU share the array, which needs no clearing between calls (every record a call reads it has
+ * written itself): calls that overlap in time on one GPU, on whatever streams, race -- serialise them.
+ */
+int attn_decode_paged_static(const attn_args *args, void *hip_stream);
+/* Size of that array in bytes (pure host function). */
+size_t attn_static_scratch_bytes(void);
+
+/*
  * The step in front of paged attention: stores the keys and values of new tokens into the paged
  * cache (the PagedAttention layout the paper cites; the paper itself is silent on this step).
  * Token t goes to slot slot_mapping[t] = block * block_size + offset of both caches; a negative slot

@@ -78,6 +78,10 @@ def load_library():
     lib.attn_prefill_varlen.argtypes = [P, ctypes.c_void_p]
     lib.attn_decode_paged.restype = ctypes.c_int
     lib.attn_decode_paged.argtypes = [P, ctypes.c_void_p]
+    lib.attn_decode_paged_static.restype = ctypes.c_int
+    lib.attn_decode_paged_static.argtypes = [P, ctypes.c_void_p]
+    lib.attn_static_scratch_bytes.restype = ctypes.c_size_t
+    lib.attn_static_scratch_bytes.argtypes = []
     lib.attn_workspace_bytes.restype = ctypes.c_size_t
     lib.attn_workspace_bytes.argtypes = [P, ctypes.c_int]
     lib.attn_tune.restype = ctypes.c_int
@@ -255,6 +259,21 @@ def attn_decode_paged(q, k_cache, v_cache, out, block_table, seq_lens, scale, *,
     rc = load_library().attn_decode_paged(ctypes.byref(a), _stream_ptr(stream))
     if rc != 0:
         raise AttnError(rc, "attn_decode_paged")
+
+
+def attn_decode_paged_static(q, k_cache, v_cache, out, block_table, seq_lens, scale, *, max_kv_len, stream=None,
+                             args: Optional[AttnArgs] = None) -> None:
+    """attn_decode_paged with the split-K records in the library's own static device array: no workspace
+    argument, nothing allocated."""
+    a = args or make_args(q, k_cache, v_cache, out, seq_lens, scale, max_q_len=1, max_kv_len=max_kv_len,
+                          block_table=block_table, causal=True, is_decode=True)
+    rc = load_library().attn_decode_paged_static(ctypes.byref(a), _stream_ptr(stream))
+    if rc != 0:
+        raise AttnError(rc, "attn_decode_paged_static")
+
+
+def attn_static_scratch_bytes() -> int:
+    return int(load_library().attn_static_scratch_bytes())
 
 
 def attn_workspace_bytes(args: AttnArgs, is_decode: bool) -> int:

@@ -1023,7 +1023,64 @@ const Instance *prefill_instances(int *count)
 
 using namespace attn;
 
+// ---- the entry point that allocates nothing ------------------------------------------------------
+// Split-K records of attn_decode_paged_static live in this array instead of a caller workspace.  Every
+// GPU the library runs on holds its own copy, at its own address, until the process ends.  In host
+// code the name `scratch` is only a handle for hipGetSymbolAddress, never a device address.
+constexpr size_t kScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device, resolved once per device (with that device
+// current); nullptr if the runtime refuses.
+void *scratch_on_current_device()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
 extern "C" {
+
+int attn_decode_paged_static(const attn_args *args, void *hip_stream)
+{
+    int rc = validate(args, 1);
+    if (rc != ATTN_OK) return rc;
+    if (args->num_seqs == 0 || args->total_q == 0) return ATTN_OK;
+    // the need of the instance this call will take, against the fixed size of the array
+    const KParams p = to_kparams(args, 1);
+    int n;
+    const Instance *t = instances(1, &n);
+    const int id = select_instance(p, args->dtype, 1);
+    if (id < 0) return id;
+    if (id >= n || !usable(t[id], p, 1)) return ATTN_ERR_UNSUPPORTED;
+    if (instance_workspace_bytes(t[id], p) > kScratchBytes) return ATTN_ERR_WORKSPACE;
+    void *ptr = scratch_on_current_device();
+    if (!ptr) return ATTN_ERR_HIP;
+    attn_args a = *args;
+    a.workspace = ptr;
+    a.workspace_bytes = kScratchBytes;
+    return run(&a, 1, (hipStream_t)hip_stream, id);
+}
+
+size_t attn_static_scratch_bytes(void) { return kScratchBytes; }
 
 int attn_prefill_varlen(const attn_args *args, void *hip_stream) { return run(args, 0, (hipStream_t)hip_stream, -1); }
 
