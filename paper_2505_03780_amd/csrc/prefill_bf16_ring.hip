@@ -30,8 +30,8 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-// The two 16-bit element types the kernel is instantiated for: how a 32x32x16 product, the packing of
-// two weights and the sum of a packed pair are spelled.  Everything else (transfers, swizzles,
+// The two 16-bit element types the kernel is instantiated for: how a 32x32x16 product and the packing
+// of two weights are spelled.  Everything else (transfers, swizzles,
 // transposing reads, masks, the fp32 softmax) is the same code.
 struct ElemBf16 {
     typedef __bf16 elem;
@@ -39,7 +39,6 @@ struct ElemBf16 {
     typedef bf16x2 x2;
     static constexpr int kDtype = kDtypeBf16;
     static __device__ __forceinline__ f32x16 mfma(x8 a, x8 b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
-    static __device__ __forceinline__ float dot2(x2 a, x2 b, float c) { return __builtin_amdgcn_fdot2_f32_bf16(a, b, c, false); }
 };
 struct ElemF16 {
     typedef _Float16 elem;
@@ -47,7 +46,6 @@ struct ElemF16 {
     typedef f16x2 x2;
     static constexpr int kDtype = kDtypeF16;
     static __device__ __forceinline__ f32x16 mfma(x8 a, x8 b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
-    static __device__ __forceinline__ float dot2(x2 a, x2 b, float c) { return __builtin_amdgcn_fdot2(a, b, c, false); }
 };
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
@@ -79,10 +77,14 @@ __device__ __forceinline__ float swap32_sum(float x)
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// Transposing LDS read issued behind the compiler's back.  The compiler cannot tell that this read
-// never touches a ring slot with a transfer in flight and would drain the whole prefetch queue
-// (s_waitcnt vmcnt(0)) in front of the builtin; as inline assembly it is not tracked at all, so the
-// consumer must wait for it explicitly with lds_wait() before using the value.
+// LDS traffic of the unit loop is issued behind the compiler's back, as inline assembly, and waited
+// for by count.  Two reasons.  The compiler cannot tell that a transposing read never touches a ring
+// slot with a transfer in flight and would drain the whole prefetch queue (s_waitcnt vmcnt(0)) in
+// front of the builtin.  And once any of the loop's LDS operations is hidden from it, it waits for
+// the ones it still sees with lgkmcnt(0), i.e. for the read it issued a moment ago, several times per
+// unit.  LDS operations of a wave complete in order, so "at most N operations outstanding" means
+// that everything but the N youngest has returned: every consumer below waits with the number of LDS
+// operations issued after the one it needs (lds_wait), counted at compile time along the unrolled code.
 __device__ __forceinline__ s16x4 lds_read_tr16_b64_untracked(const unsigned char *p)
 {
     s16x4 r;
@@ -90,8 +92,37 @@ __device__ __forceinline__ s16x4 lds_read_tr16_b64_untracked(const unsigned char
     asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(r) : "v"(addr) : "memory");
     return r;
 }
+__device__ __forceinline__ unsigned lds_addr(const unsigned char *p)
+{
+    return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const unsigned char *)p;
+}
+template <int OFFSET>
+__device__ __forceinline__ u32x4 lds_read_b128_untracked(unsigned addr)
+{
+    u32x4 r;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFFSET) : "memory");
+    return r;
+}
+__device__ __forceinline__ void lds_write_b128_untracked(unsigned addr, s16x8 v)
+{
+    asm volatile("ds_write_b128 %0, %1" : : "v"(addr), "v"(v) : "memory");
+}
 // all LDS operations of this wave have returned; ties the registers so that their uses stay below
 __device__ __forceinline__ void lds_wait(s16x4 &a, s16x4 &b) { asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b)::"memory"); }
+// at most n LDS operations of this wave are still outstanding (n is a constant once the loops around
+// the call are unrolled, so the switch folds to one instruction); `r` is tied so that its use stays below
+template <typename T>
+__device__ __forceinline__ void lds_wait_upto(int n, T &r)
+{
+#define LDS_WAIT_CASE(N) case N: asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(r)::"memory"); break;
+    switch (n < 0 ? 0 : n) {
+        LDS_WAIT_CASE(0) LDS_WAIT_CASE(1) LDS_WAIT_CASE(2) LDS_WAIT_CASE(3) LDS_WAIT_CASE(4) LDS_WAIT_CASE(5) LDS_WAIT_CASE(6)
+        LDS_WAIT_CASE(7) LDS_WAIT_CASE(8) LDS_WAIT_CASE(9) LDS_WAIT_CASE(10) LDS_WAIT_CASE(11) LDS_WAIT_CASE(12) LDS_WAIT_CASE(13)
+        LDS_WAIT_CASE(14)
+        default: asm volatile("s_waitcnt lgkmcnt(15)" : "+v"(r)::"memory"); break;  // the counter's largest value
+    }
+#undef LDS_WAIT_CASE
+}
 
 // s_waitcnt with only vmcnt constrained (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
 template <int N>
@@ -267,6 +298,18 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
         row = row < n_kv ? row : n_kv - 1;
         return bt_row[__builtin_amdgcn_readfirstlane(row) >> p.block_shift];
     };
+    // The same entry, requested with an untracked scalar load (inline assembly): the value may only be
+    // used after an s_waitcnt lgkmcnt(0) that follows the request (scalar loads return out of order).
+    auto table_entry_request = [&](int unit) -> int {
+        if (!PAGED) return 0;
+        int u0 = unit * kUnit < last_unit0 ? unit * kUnit : last_unit0;
+        int row = u0 + RPW * wave;
+        row = row < n_kv ? row : n_kv - 1;
+        const unsigned byte_off = (unsigned)(__builtin_amdgcn_readfirstlane(row) >> p.block_shift) * 4u;
+        int r;
+        asm volatile("s_load_dword %0, %1, %2" : "=s"(r) : "s"(bt_row), "s"(byte_off) : "memory");
+        return r;
+    };
     auto issue_unit = [&](int unit, int entry) {
         unsigned char *slot = lds + (unit % NSLOT) * kSlotBytes + RPW * wave * 256;
         const int u0 = unit * kUnit < last_unit0 ? unit * kUnit : last_unit0;  // units past the end repeat the last one
@@ -418,30 +461,6 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
         }
         move_reference(bm);
     };
-    // P = 2^(x - ref) as bf16 B operands; row sums are taken over the rounded values
-    auto exponentiate = [&](const f32x16 (&sacc)[QB], x8 (&pf)[QB][2], auto mask_tag) {
-        constexpr bool MASK = decltype(mask_tag)::value;
-        x2 ones;
-        ones[0] = (elem)1.f;
-        ones[1] = (elem)1.f;
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            float sum = 0.f;
-#pragma unroll
-            for (int v = 0; v < 16; v += 2) {
-                const float e0 = fast_exp2(MASK ? sacc[qb][v] - m_ref[qb] : __builtin_fmaf(sacc[qb][v], c, -m_ref[qb]));
-                const float e1 = fast_exp2(MASK ? sacc[qb][v + 1] - m_ref[qb] : __builtin_fmaf(sacc[qb][v + 1], c, -m_ref[qb]));
-                x2 pr;
-                pr[0] = (elem)e0;
-                pr[1] = (elem)e1;
-                sum = E::dot2(pr, ones, sum);
-                pf[qb][v >> 3][v & 7] = pr[0];
-                pf[qb][v >> 3][(v & 7) + 1] = pr[1];
-            }
-            l_run[qb] += sum;
-        }
-    };
-
     // ---- prologue: PF units in flight, S(0) ready ------------------------------------------------
 #pragma unroll
     for (int u = 0; u < PF; ++u) issue_unit(u, table_entry(u));
@@ -454,13 +473,15 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
         settle(0, s_cur, Masked{});
     else
         settle(0, s_cur, Plain{});
-    x8 kf[KSTEPS];  // K fragments of the next unit, fetched one iteration ahead
+    u32x4 kf[KSTEPS];  // K fragments of the next unit, fetched one iteration ahead
 #pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) kf[ks] = *(const x8 *)(lds + (1 % NSLOT) * kSlotBytes + koff[ks]);
+    for (int ks = 0; ks < KSTEPS; ++ks) kf[ks] = *(const u32x4 *)(lds + (1 % NSLOT) * kSlotBytes + koff[ks]);
+    int entry_cur = table_entry(PF);  // (a tracked scalar load: the wait below covers it)
     {
         s16x4 raw[C::kFragsPerWave][2];
         transpose_load(0, raw);
         transpose_store(0, raw);
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(entry_cur)::"memory");
         __builtin_amdgcn_s_waitcnt(0xC07F);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
@@ -480,24 +501,42 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
     // Invariant at the top of iteration u: S(u) settled in `cur`; kf = K(u+1); units <= u+2 resident;
     // units <= u+PF-1 issued.  S(u+1) is computed even past the last unit (its ring slot then holds the
     // re-read rows of a dummy transfer and every entry is masked): no branch inside the iteration.
+    // LDS operations of one iteration, in issue order (the same in every iteration, so the position of
+    // an operation of the previous iteration is known too):
+    //   phase X: V^T image fragments f = 0..7 (one per 1/8 of the phase), after fragment 1 the wave's
+    //            transposing reads of V(u+1) (2 per fragment it owns), after fragment kWriteAfter the
+    //            wave's image stores of V(u+1);
+    //   phase Y: K(u+2) fragments ks = 0..7, kKPerGroup per group from the first group on.
+    // A consumer waits until at most as many operations are outstanding as were issued after the one it
+    // needs.  Nothing in the loop waits for "all": the image stores are older than the last image
+    // fragments the same wave waits for in phase Y, so they have been performed when the wave reaches
+    // the barrier; the K reads stay in flight across the barrier.
+    constexpr int kWriteAfter = 5;
+    constexpr int kXOps = 8 + 3 * C::kFragsPerWave;  // LDS operations of phase X
+    constexpr int kKPerGroup = 2;
+    // Block-table entry of the unit that the next iteration transfers (entry_cur, set up in the prologue):
+    // requested (scalar cache) at the top of an iteration, awaited at its barrier -- the one place where
+    // this wave waits for everything it has in flight, because scalar loads share the LDS counter and
+    // return out of order.
     auto iteration = [&](int u, f32x16 (&cur)[QB], f32x16 (&nxt)[QB], auto cur_tag, auto nxt_tag) {
         constexpr bool CUR_MASK = decltype(cur_tag)::value;
         constexpr bool NXT_MASK = decltype(nxt_tag)::value;
         constexpr int G = 8 * QB;  // MFMAs per product
-        const unsigned char *img = img_base + (u & 1) * C::kImgBytes + lane * 16;
+        const unsigned img_rd = lds_addr(img_base + (u & 1) * C::kImgBytes + lane * 16);
+        const unsigned img_wr = lds_addr(img_base + ((u + 1) & 1) * C::kImgBytes + lane * 16);
         const unsigned char *kt2 = lds + ((u + 2) % NSLOT) * kSlotBytes;
-        const int entry = table_entry(u + PF);  // scalar load, consumed at the end of phase Y
 
         x8 pf[QB][2];
-        x8 vfrag[2 * DB];
+        u32x4 vfrag[2 * DB];
         s16x4 raw[C::kFragsPerWave][2];
-        float sum[QB];
-        x2 ones;
-        ones[0] = (elem)1.f;
-        ones[1] = (elem)1.f;
+        float sum[QB][2];
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) sum[qb] = 0.f;
+        for (int qb = 0; qb < QB; ++qb) sum[qb][0] = sum[qb][1] = 0.f;
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        int seq = 0;        // LDS operations issued so far in this iteration
+        int vpos[2 * DB];   // position of image fragment f in this iteration's sequence
+        int tr_last = 0;    // position of the last transposing read
+        int entry_nxt = table_entry_request(u + 1 + PF);
         // weights 2p, 2p+1 of row block qb: exponentials, rounding, row sum.  The exponentials are spread over
         // both phases (half under the score MFMAs, half under the first PV MFMAs, which only need the
         // first half), so that neither phase has more vector work than matrix work to hide it under.
@@ -508,20 +547,51 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
             x2 pr;
             pr[0] = (elem)e0;
             pr[1] = (elem)e1;
-            sum[qb] = E::dot2(pr, ones, sum[qb]);
+            // Row sums with plain adds, two chains per row block (even and odd pairs).  The dot-product
+            // instruction that would sum the rounded pair in one go occupies the matrix pipe for about
+            // half an MFMA (measured), so it is not free under the MFMAs; the sum of the unrounded
+            // weights differs from the sum of the rounded ones by rounding errors that average out.
+            sum[qb][pair & 1] += e0 + e1;
             pf[qb][v >> 3][v & 7] = pr[0];
             pf[qb][v >> 3][(v & 7) + 1] = pr[1];
         };
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const int ks = g / QB, qb = g % QB;
-            nxt[qb] = E::mfma(kf[ks], qf[qb][ks], ks == 0 ? zero : nxt[qb]);
+            // K(u+1) fragment ks was read in phase Y of the previous iteration, at position kXOps + ks of
+            // kXOps + 8; since then the rest of that iteration and `seq` operations of this one were issued
+            if (qb == 0) lds_wait_upto((KSTEPS - 1 - ks) + seq, kf[ks]);
+            nxt[qb] = E::mfma(__builtin_bit_cast(x8, kf[ks]), qf[qb][ks], ks == 0 ? zero : nxt[qb]);
             if (ks % 2 == 0) exp_pair(qb, ks / 2);  // weights of keys 0..15: the B operand of the first four PV MFMAs
             if (g * 8 / G != (g + 1) * 8 / G) {
                 const int f = g * 8 / G;
-                vfrag[f] = *(const x8 *)(img + f * 1024);
+                switch (f) {  // the fragment index becomes the instruction's immediate offset
+                    case 0: vfrag[0] = lds_read_b128_untracked<0 * 1024>(img_rd); break;
+                    case 1: vfrag[1] = lds_read_b128_untracked<1 * 1024>(img_rd); break;
+                    case 2: vfrag[2] = lds_read_b128_untracked<2 * 1024>(img_rd); break;
+                    case 3: vfrag[3] = lds_read_b128_untracked<3 * 1024>(img_rd); break;
+                    case 4: vfrag[4] = lds_read_b128_untracked<4 * 1024>(img_rd); break;
+                    case 5: vfrag[5] = lds_read_b128_untracked<5 * 1024>(img_rd); break;
+                    case 6: vfrag[6] = lds_read_b128_untracked<6 * 1024>(img_rd); break;
+                    default: vfrag[7] = lds_read_b128_untracked<7 * 1024>(img_rd); break;
+                }
+                vpos[f] = seq++;
+                if (f == 1) {  // this wave's share of V(u+1): transposed here, stored a few groups later
+                    transpose_load(u + 1, raw);
+                    seq += 2 * C::kFragsPerWave;
+                    tr_last = seq - 1;
+                }
+                if (f == kWriteAfter) {  // image (u+1)&1 was last read in iteration u-1, before the barrier
+#pragma unroll
+                    for (int i = 0; i < C::kFragsPerWave; ++i) {
+                        lds_wait_upto(seq - 1 - tr_last, raw[i][0]);
+                        lds_wait_upto(15, raw[i][1]);  // already there: only ties the register below the wait
+                        const s16x8 both = __builtin_shufflevector(raw[i][0], raw[i][1], 0, 1, 2, 3, 4, 5, 6, 7);
+                        lds_write_b128_untracked(img_wr + (wave * C::kFragsPerWave + i) * 1024, both);
+                        ++seq;
+                    }
+                }
             }
-            if (g == 1) transpose_load(u + 1, raw);  // this wave's share of V(u+1), stored late in phase Y
             __builtin_amdgcn_sched_barrier(0);
         }
 
@@ -532,7 +602,8 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const int f = g / QB, qb = g % QB;  // f = ks2 * DB + db
-            oacc[qb][f % DB] = E::mfma(vfrag[f], pf[qb][f / DB], oacc[qb][f % DB]);
+            if (qb == 0) lds_wait_upto(seq - 1 - vpos[f], vfrag[f]);
+            oacc[qb][f % DB] = E::mfma(__builtin_bit_cast(x8, vfrag[f]), pf[qb][f / DB], oacc[qb][f % DB]);
             if (f < DB) exp_pair(qb, 4 + f);  // weights of keys 16..31, needed from the fifth PV MFMA on
             const int sl = g - 4 * QB;  // the second half of the phase: the last S MFMAs have drained
             if (sl >= 0 && sl < 4 * QB) {
@@ -547,17 +618,21 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
                 const float m3 = fmaxf(fmaxf(nxt[q2][v0], nxt[q2][v0 + 1]), nxt[q2][v0 + 2]);
                 mx[q2] = v0 == 0 ? fmaxf(m3, nxt[q2][v0 + 3]) : fmaxf(fmaxf(mx[q2], m3), nxt[q2][v0 + 3]);
             }
-            // K fragments of unit u+2, one per group (the fragments of u+1 were consumed in phase X)
-            if (g * KSTEPS / G != (g + 1) * KSTEPS / G) {
-                const int ks = g * KSTEPS / G;
-                kf[ks] = *(const x8 *)(kt2 + koff[ks]);
+            // K fragments of unit u+2 (the fragments of u+1 were consumed in phase X), in order, early in
+            // the phase: they are a few groups old when the next iteration asks for them
+#pragma unroll
+            for (int j = 0; j < kKPerGroup; ++j) {
+                const int ks = g * kKPerGroup + j;
+                if (ks < KSTEPS) {
+                    kf[ks] = lds_read_b128_untracked<0>(lds_addr(kt2 + koff[ks]));
+                    ++seq;
+                }
             }
-            if (g == G - 3) issue_unit(u + PF, entry);  // refill: unit u+PF replaces unit u+PF-NSLOT <= u
-            if (g == G - 2) transpose_store(u + 1, raw);  // image (u+1)&1 was last read in iteration u-1
+            if (g == G - 3) issue_unit(u + PF, entry_cur);  // refill: unit u+PF replaces unit u+PF-NSLOT <= u
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) l_run[qb] += sum[qb];
+        for (int qb = 0; qb < QB; ++qb) l_run[qb] += sum[qb][0] + sum[qb][1];
         float bm[QB];
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
@@ -565,7 +640,14 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
             bm[qb] = NXT_MASK ? m : m * c;
         }
         move_reference(bm);
-        ring_barrier();
+        // Publish.  This wave's transfers of every unit but the newest PF-3 have landed (see ring_barrier);
+        // its image stores have been performed (phase Y waited for younger reads); its K reads may still
+        // be in flight, they target a slot that no transfer touches before the barrier after next.
+        wait_vmcnt<2 * NDMA * (PF - 3)>();
+        if (PAGED) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(entry_nxt)::"memory");
+        entry_cur = entry_nxt;
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
     };
     auto copy_back = [&]() {
 #pragma unroll
@@ -592,6 +674,12 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
         iteration(u + 1, s_nxt, s_cur, Masked{}, Masked{});
     }
     if (u < n_units) iteration(u, s_cur, s_nxt, Masked{}, Masked{});
+    // The last iteration's K reads are still in flight and nobody will use them: wait for them here,
+    // with their registers tied, so that the compiler cannot hand those registers to anything else
+    // while a read may still land in them.
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]), "+v"(kf[4]), "+v"(kf[5]), "+v"(kf[6]), "+v"(kf[7])::"memory");
+    static_assert(KSTEPS == 8, "the drain above names eight fragments");
 
     // ---- epilogue: O / l, transposed through LDS, whole rows to HBM ------------------------------
     wait_vmcnt<0>();
@@ -700,8 +788,7 @@ const Instance *prefill_ring_f16_instances(int *count)
 const Instance *prefill_ring_instances(int *count)
 {
     static const Instance table[] = {
-        RING_INSTANCE(2, 4, 8, 5, 4), RING_INSTANCE(2, 2, 8, 5, 4), RING_INSTANCE(2, 1, 8, 5, 4),
-        RING_INSTANCE(2, 4, 8, 6, 4), RING_INSTANCE(1, 4, 8, 5, 8), RING_INSTANCE(1, 8, 8, 5, 8),
+        RING_INSTANCE(1, 4, 8, 5, 8), RING_INSTANCE(1, 8, 8, 5, 8),
         RING_INSTANCE(1, 2, 8, 5, 8), RING_INSTANCE(1, 1, 8, 5, 8), RING_INSTANCE(1, 4, 8, 6, 8),
         RING_INSTANCE(1, 4, 8, 8, 8), RING_INSTANCE(1, 1, 8, 8, 8), RING_INSTANCE(1, 4, 4, 4, 4),
         RING_INSTANCE(1, 1, 4, 4, 4), RING_INSTANCE(1, 2, 4, 4, 4),
