@@ -328,8 +328,17 @@ def measure(wl_id: int, steps: int, warmup: int, tune: bool, check: bool = True)
     if tune:
         u = _figures(wl, run, *time_steps(run, max(5, steps // 3), warmup))
         untuned = {"instance": u["instance"], "value": u["value"], "kernel_ms_mean": u["kernel_ms_mean"]}
-        run.A.attn_tune(run.args[0], run.is_decode, os.environ.get("ATTN_TUNE_CACHE"), 10, 0)
+        run.A.attn_tune(run.args[0], run.is_decode, os.environ.get("ATTN_TUNE_CACHE"), 20, 0)
         run.instance = run.A.attn_instance_name(run.is_decode, run.A.attn_selected_instance(run.args[0], run.is_decode))
+        # the tuner has just allocated and freed gigabytes and left the chip idle while it did: bring the
+        # clocks up again exactly as before the first leg (the W warm-up steps alone are too short for
+        # that: without it the same instance measured 3 % slower after tuning than before)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < 0.3:
+            for _ in range(20):
+                run.step(sp)
+            torch.cuda.synchronize()
     res = _figures(wl, run, *time_steps(run, steps, warmup))
     res["untuned"] = untuned
     res["check"] = check_output(wl, run) if check else None

@@ -190,12 +190,14 @@ size_t attn_workspace_bytes(const attn_args *args, int is_decode);
  * prefill) query_start_loc are used, if not NULL: the tuning batch then has the
  * caller's own lengths (copied to the host; they must respect max_q_len and
  * max_kv_len).  Otherwise lengths are spread evenly between half of and the full
- * max_q_len / max_kv_len.  The search is a successive halving: three timed
- * launches of every valid instance, iters/2 of the best third (the built-in
- * choice and the winners already known for neighbouring buckets always stay in),
- * `iters` (<= 0: a default) of the best three; an instance three times slower
- * than the best so far is dropped after one launch; the built-in choice wins
- * ties within 2 % (launch-to-launch noise).  The call records the
+ * max_q_len / max_kv_len.  Paged tuning batches use a random permutation of the
+ * block pool.  The search is a successive halving: three timed launches of every
+ * valid instance, iters/2 of the best third (the built-in choice and the winners
+ * already known for neighbouring buckets always stay in); an instance three times
+ * slower than the best so far is dropped after one launch.  The best three and the
+ * built-in choice are then measured `iters` (<= 0: a default) more times each,
+ * taking turns launch by launch, and the medians decide; the built-in choice wins
+ * ties within 3 % (launch-to-launch noise).  The call records the
  * fastest instance and, if cache_path is not NULL, merges it into that file:
  * read, change and replace (write to a temporary file, fsync, rename) under an
  * exclusive flock on "<cache_path>.lock", so concurrent tuners keep each other's
