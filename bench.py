@@ -75,7 +75,8 @@ def summarize_traffic(directory: str, workload: str):
                     a[1] += 1
         return {k: v[0] / v[1] for k, v in agg.items()}
 
-    ours = lambda n: "attn::" in n
+    # the library's kernels, without the probes and the tuner's fill kernels
+    ours = lambda n: "attn::" in n and not any(x in n for x in ("hbm_read_kernel", "mfma_bf16_kernel", "fill_bf16_kernel", "fill_f16_kernel"))
     copy = lambda n: "copyBuffer" in n
     out = {}
     for counter in ("FETCH_SIZE", "WRITE_SIZE"):
@@ -453,8 +454,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", choices=sorted(WORKLOADS) + ["rmsnorm"], default="c2",
-                    help="c2..c5: attention configurations (c2 is the headline); rmsnorm: only the fused RMS norm leg")
+    ap.add_argument("--workload", choices=sorted(WORKLOADS) + ["rmsnorm", "rmsnorm_h8192"], default="c2",
+                    help="c2..c5: attention configurations (c2 is the headline); rmsnorm, rmsnorm_h8192: only the fused RMS norm "
+                         "leg at hidden 4096 or 8192")
     ap.add_argument("--no-extra", action="store_true", help="skip the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-tune", action="store_true", help="keep the built-in heuristic (default: attn_tune runs first, untimed)")
@@ -486,8 +488,8 @@ def main():
         print(json.dumps({"copy_probe_bytes_read": 1 << 30, "copy_probe_bytes_written": 1 << 30, "copies": 3}))
         return
 
-    if a.workload == "rmsnorm":
-        r = measure_rmsnorm(a.steps, a.warmup, not a.no_tune)
+    if a.workload.startswith("rmsnorm"):
+        r = measure_rmsnorm(a.steps, a.warmup, not a.no_tune, 8192 if a.workload.endswith("8192") else 4096)
         print(json.dumps({"metric": r["metric"], "value": r["value"], "unit": r["unit"], "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
                           "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
                           "dtype": "bf16", "data": "synthetic", "config": {"workload": r["workload"], "instance": r["instance"]},
