@@ -276,12 +276,19 @@ __global__ __launch_bounds__(WAVES * 64) void decode_bf16_kernel(const KParams p
     }
 }
 
-// Streams keys [k_lo, k_hi) of sequence s for KV head kvh through one wavefront and leaves the result
-// either as fp32 (partial output, max, sum) records, the one of query head h at partial_base +
-// h * head_stride, or, if partial_base is null, as the final bf16 output.
-template <int HD, int WAVES>
-__device__ __forceinline__ void decode_stream_part(const KParams &p, unsigned char *vst, int lane, int s, int kvh, int n_kv,
-                                                   int k_lo, int k_hi, float *partial_base, int64_t head_stride)
+// Streams a run of `nrun` 32-key chunks for KV head kvh through one wavefront.  The run starts `off0`
+// chunks into sequence s0 and may go on through any number of following sequences (the token-balanced
+// kernel's unit of work; the wave-per-head kernel passes one part of one sequence).  The chunks a run
+// takes from one sequence are a piece; a piece ends with the sequence or with the run.
+// Each piece leaves either fp32 (partial output, max, sum) records, the one of query head h at
+// record(s, whole) + h * head_stride, or, where record(s, whole) returns null, the final output row
+// (`whole` says that the piece holds every key of sequence s).
+// The load pipeline does not stop where one sequence ends and the next begins: the chunks of the next
+// piece are requested two steps ahead like any others, so all a wavefront waits for at a boundary is
+// the next sequence's query row.  Sequences without keys inside the run are skipped.
+template <int HD, int WAVES, class Record>
+__device__ __forceinline__ void decode_stream_run(const KParams &p, unsigned char *vst, int lane, int kvh, int s0, int off0, int nrun,
+                                                  Record record, int64_t head_stride)
 {
     using C = DecodeCfg<HD, WAVES>;
     constexpr int KS = HD / 32;
@@ -292,29 +299,89 @@ __device__ __forceinline__ void decode_stream_part(const KParams &p, unsigned ch
     const int l16 = lane & 15;
     const int lg = lane >> 4;
     const int G = p.group;
+    const int B = p.num_seqs;
+    const unsigned char *kbase = (const unsigned char *)p.k + (int64_t)kvh * p.kv_stride_head * 2;
+    const unsigned char *vbase = (const unsigned char *)p.v + (int64_t)kvh * p.kv_stride_head * 2;
+    const uint32_t tok_bytes = (uint32_t)p.kv_stride_tok * 2;
+    table_ptr lens = (table_ptr)p.seq_lens;
 
-    if (k_hi <= k_lo) {  // no key (an empty context): the empty result, and no table entry is touched
-        if (l16 < G) {
-            const int head = kvh * G + l16;
-            if (partial_base == nullptr) {
-                elem_t *o = (elem_t *)p.out + (int64_t)s * p.o_stride_tok + (int64_t)head * p.o_stride_head;
-                for (int d = 4 * lg; d < HD; d += 16) *(uint2 *)(o + d) = uint2{0u, 0u};
-            } else {
-                float *w = partial_base + (int64_t)head * head_stride;
-                for (int d = 4 * lg; d < HD; d += 16) {
-                    *(float2 *)(w + d) = float2{0.f, 0.f};
-                    *(float2 *)(w + d + 2) = float2{0.f, 0.f};
-                }
-                if (lg == 0) *(float2 *)(w + HD) = float2{-INFINITY, 0.f};
-            }
-        }
-        return;
+    // per-lane byte offsets inside a 16-key group, the same for K and V: whole head slices, fully coalesced
+    uint32_t v_lane[VLD];
+#pragma unroll
+    for (int i = 0; i < VLD; ++i) {
+        const int row = lane / (HD / 8) + VROWS * i;
+        v_lane[i] = (uint32_t)(row & 15) * tok_bytes + 16 * (lane % (HD / 8));
     }
 
+    // ---- load cursor: the chunk whose addresses are worked out next ---------------------------------
+    int ld_s = s0, ld_key = off0 * kChunk, ld_left = nrun;  // sequence, first key of the chunk, chunks still to address
+    int ld_nkv = lens[s0];
+    table_ptr ld_row = (table_ptr)(p.block_table + (int64_t)s0 * p.block_table_stride);
+    struct Bases {
+        int64_t g0, g1;
+    };
+    // byte offsets (wave-uniform) of the two 16-key groups of the next chunk of the run; groups past the
+    // end of their sequence fall back to its last real group, whose rows are allocated (and masked)
+    auto next_bases = [&]() -> Bases {
+        if (ld_left <= 0) return Bases{0, 0};
+        const int last_group = (ld_nkv - 1) & ~15;
+        auto base = [&](int key) -> int64_t {
+            key = key < last_group ? key : last_group;
+            const int blk = ld_row[key >> p.block_shift];
+            return (int64_t)blk * p.kv_stride_block * 2 + (int64_t)(key & (p.block_size - 1)) * tok_bytes;
+        };
+        const Bases b{base(ld_key), base(ld_key + 16)};
+        ld_key += kChunk;
+        --ld_left;
+        if (ld_key >= ld_nkv && ld_left > 0) {  // on to the next sequence that has keys
+            do {
+                ++ld_s;
+                ld_nkv = lens[ld_s < B ? ld_s : B - 1];
+            } while (ld_nkv <= 0 && ld_s < B - 1);
+            if (ld_nkv <= 0) ld_left = 0;  // (lengths that changed under the kernel: stop rather than run on)
+            ld_row = (table_ptr)(p.block_table + (int64_t)ld_s * p.block_table_stride);
+            ld_key = 0;
+        }
+        return b;
+    };
+
+    struct Regs {
+        u32x4 k[2][KS];
+        u32x4 v[VLD];
+    };
+    auto load = [&](Regs &r, const Bases &b) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+#pragma unroll
+            for (int i = 0; i < KS; ++i) r.k[t][i] = kv_load(kbase + (t ? b.g1 : b.g0) + v_lane[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < VLD; ++i) {
+            const int row = lane / (HD / 8) + VROWS * i;
+            r.v[i] = kv_load(vbase + (row < 16 ? b.g0 : b.g1) + v_lane[i]);
+        }
+    };
+
+    // ---- consume cursor: the piece whose chunks are being multiplied --------------------------------
+    int cs = s0 - 1, c_key = 0, c_hi = 0, c_left = nrun;  // sequence, next key, end of the piece, chunks still to consume
+    bool c_whole = false;
+    int c_off = off0;
     ex8 qf[KS];
-    {
-        const elem_t *qrow = (const elem_t *)p.q + (int64_t)s * p.q_stride_tok +
-                             (int64_t)(kvh * G + (l16 < G ? l16 : 0)) * p.q_stride_head + 8 * lg;
+    f32x4 oacc[DB];
+    float m_run = -INFINITY, l_run = 0.f;
+    auto begin_piece = [&]() {
+        int n_kv;
+        do {
+            ++cs;
+            n_kv = lens[cs < B ? cs : B - 1];
+        } while (n_kv <= 0 && cs < B - 1);
+        const int nc = (n_kv + kChunk - 1) / kChunk;
+        const int n = c_left < nc - c_off ? c_left : nc - c_off;
+        c_key = c_off * kChunk;
+        c_hi = (c_off + n) * kChunk < n_kv ? (c_off + n) * kChunk : n_kv;
+        c_whole = n == nc;
+        c_off = 0;
+        const elem_t *qrow = (const elem_t *)p.q + (int64_t)cs * p.q_stride_tok + (int64_t)(kvh * G + (l16 < G ? l16 : 0)) * p.q_stride_head + 8 * lg;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             ex8 t = *(const ex8 *)(qrow + 32 * ks);
@@ -324,56 +391,46 @@ __device__ __forceinline__ void decode_stream_part(const KParams &p, unsigned ch
             }
             qf[ks] = t;
         }
-    }
-
-    const unsigned char *kbase = (const unsigned char *)p.k + (int64_t)kvh * p.kv_stride_head * 2;
-    const unsigned char *vbase = (const unsigned char *)p.v + (int64_t)kvh * p.kv_stride_head * 2;
-    table_ptr bt_row = (table_ptr)(p.block_table + (int64_t)s * p.block_table_stride);
-    const uint32_t tok_bytes = (uint32_t)p.kv_stride_tok * 2;
-    const int last_group = (n_kv - 1) & ~15;  // first key of the last 16-key group that holds a real key
-
-    // byte offset (wave-uniform) of the first row of the 16-key group at `key`; groups past the end of
-    // the sequence fall back to the last real group, whose rows are allocated (and masked)
-    auto group_base = [&](int key) -> int64_t {
-        key = key < last_group ? key : last_group;
-        const int blk = bt_row[key >> p.block_shift];
-        return (int64_t)blk * p.kv_stride_block * 2 + (int64_t)(key & (p.block_size - 1)) * tok_bytes;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) oacc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+        m_run = -INFINITY;
+        l_run = 0.f;
     };
-    // per-lane byte offsets inside a group, the same for K and V: whole head slices, fully coalesced
-    uint32_t v_lane[VLD];
+    // this wave's result for the piece: G heads x HD channels, no other wave involved
+    auto end_piece = [&]() {
+        float l_all = l_run + __shfl_xor(l_run, 16);
+        l_all += __shfl_xor(l_all, 32);
+        float *rec_base = record(cs, c_whole);
+        if (l16 < G) {
+            const int head = kvh * G + l16;
+            if (rec_base == nullptr) {
+                elem_t *o = (elem_t *)p.out + (int64_t)cs * p.o_stride_tok + (int64_t)head * p.o_stride_head;
+                const float inv = l_all > 0.f ? 1.f / l_all : 0.f;
 #pragma unroll
-    for (int i = 0; i < VLD; ++i) {
-        const int row = lane / (HD / 8) + VROWS * i;
-        v_lane[i] = (uint32_t)(row & 15) * tok_bytes + 16 * (lane % (HD / 8));
-    }
-
-    struct Regs {
-        u32x4 k[2][KS];
-        u32x4 v[VLD];
-    };
-    auto load = [&](Regs &r, int64_t g0, int64_t g1) {
+                for (int db = 0; db < DB; ++db) {
+                    typedef elem_t ex4 __attribute__((ext_vector_type(4)));
+                    ex4 o4;
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
+                    for (int v = 0; v < 4; ++v) o4[v] = (elem_t)(oacc[db][v] * inv);
+                    *(ex4 *)(o + db * 16 + 4 * lg) = o4;
+                }
+            } else {
+                float *rec = rec_base + (int64_t)head * head_stride;
 #pragma unroll
-            for (int i = 0; i < KS; ++i) r.k[t][i] = kv_load(kbase + (t ? g1 : g0) + v_lane[i]);
-        }
-#pragma unroll
-        for (int i = 0; i < VLD; ++i) {
-            const int row = lane / (HD / 8) + VROWS * i;
-            r.v[i] = kv_load(vbase + (row < 16 ? g0 : g1) + v_lane[i]);
+                for (int db = 0; db < DB; ++db) {
+                    // (HD + 2) floats per record: 8-byte aligned, so two 8-byte stores per block of 4
+                    *(float2 *)(rec + db * 16 + 4 * lg) = float2{oacc[db][0], oacc[db][1]};
+                    *(float2 *)(rec + db * 16 + 4 * lg + 2) = float2{oacc[db][2], oacc[db][3]};
+                }
+                if (lg == 0) *(float2 *)(rec + HD) = float2{m_run, l_all};
+            }
         }
     };
 
-    f32x4 oacc[DB];
-#pragma unroll
-    for (int db = 0; db < DB; ++db) oacc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m_run = -INFINITY, l_run = 0.f;
     const int v_rd = (4 * lg + (l16 >> 2)) * C::kVPitch + 8 * (l16 & 3);
-
     f32x4 sacc[2];
     // consume: the chunk leaves its registers (K through the wave's LDS tile into the score MFMAs, V into
-    // the tile), so
-    // the same registers can take the loads of the chunk after next right away
+    // the tile), so the same registers can take the loads of the chunk after next right away
     auto consume = [&](Regs &r, int c0) {
         // K rows arrive as whole head slices (V's wave-wide shape); the wave's LDS tile turns them into
         // MFMA operand order.  The tile is shared with V: LDS instructions of a wave execute in order,
@@ -394,17 +451,17 @@ __device__ __forceinline__ void decode_stream_part(const KParams &p, unsigned ch
                 sacc[t] = DECODE_MFMA(kf, qf[ks], sacc[t], 0, 0, 0);
             }
         }
-        const bool tail = c0 + kChunk > k_hi;
+        const bool tail = c0 + kChunk > c_hi;
 #pragma unroll
         for (int i = 0; i < VLD; ++i) {
             const int row = lane / (HD / 8) + VROWS * i;
             // rows past the end may hold anything (even NaN): their weight is 0, so store zeros
-            const u32x4 val = (tail && c0 + row >= k_hi) ? u32x4{0u, 0u, 0u, 0u} : r.v[i];
+            const u32x4 val = (tail && c0 + row >= c_hi) ? u32x4{0u, 0u, 0u, 0u} : r.v[i];
             *(u32x4 *)(vst + row * C::kVPitch + 16 * (lane % (HD / 8))) = val;
         }
     };
     auto finish = [&](int c0) {
-        const bool tail = c0 + kChunk > k_hi;
+        const bool tail = c0 + kChunk > c_hi;
         float x[8];
         float mloc = -INFINITY;
 #pragma unroll
@@ -412,22 +469,22 @@ __device__ __forceinline__ void decode_stream_part(const KParams &p, unsigned ch
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 float y = sacc[t][v] * p.scale_log2e;
-                if (tail && c0 + 16 * t + 4 * lg + v >= k_hi) y = -INFINITY;
+                if (tail && c0 + 16 * t + 4 * lg + v >= c_hi) y = -INFINITY;
                 x[4 * t + v] = y;
                 mloc = fmaxf(mloc, y);
             }
         mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
         mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-        const float m_new = fmaxf(m_run, mloc);  // finite: key c0 < k_hi is unmasked
+        const float m_new = fmaxf(m_run, mloc);  // finite: key c0 < c_hi is unmasked
         const float alpha = fast_exp2(m_run - m_new);
         m_run = m_new;
         ex8 pf;
         float rowsum = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const float w = fast_exp2(x[e] - m_new);
-            rowsum += w;
-            pf[e] = (elem_t)w;
+            const float wgt = fast_exp2(x[e] - m_new);
+            rowsum += wgt;
+            pf[e] = (elem_t)wgt;
         }
         l_run = l_run * alpha + rowsum;
 #pragma unroll
@@ -441,71 +498,67 @@ __device__ __forceinline__ void decode_stream_part(const KParams &p, unsigned ch
             oacc[db] = DECODE_MFMA(__builtin_bit_cast(ex8, both), pf, oacc[db], 0, 0, 0);
         }
     };
+    // One chunk of the run: multiply, reload the freed registers with the chunk after next, and close
+    // the piece if this was its last chunk.  Two register sets alternate, so about two chunks (32 KB
+    // per wave) are in flight; the addresses of the chunk that is loaded next are worked out (scalar
+    // loads of table entries) one step before they are needed.
+    Bases gn;
+    auto step = [&](Regs &r, bool reload) {
+        const Bases t = next_bases();
+        const int c0 = c_key;
+        consume(r, c0);
+        if (reload) load(r, gn);
+        gn = t;
+        finish(c0);
+        c_key += kChunk;
+        --c_left;
+        if (c_key >= c_hi) {
+            end_piece();
+            if (c_left > 0) begin_piece();
+        }
+    };
 
-    // chunk i covers keys [k_lo + 32 i, +32).  Two register sets alternate; a set is reloaded with the
-    // chunk after next as soon as it has been consumed, so about two chunks (32 KB per wave) are in flight.
-    const int nch = (k_hi - k_lo + kChunk - 1) / kChunk;
     Regs ra, rb;
     {
-        const int64_t a0 = group_base(k_lo), a1 = group_base(k_lo + 16);
-        const int64_t b0 = group_base(k_lo + 32), b1 = group_base(k_lo + 48);
-        if (nch > 0) load(ra, a0, a1);
-        if (nch > 1) load(rb, b0, b1);
+        const Bases a = next_bases(), b = next_bases();
+        if (nrun > 0) load(ra, a);
+        if (nrun > 1) load(rb, b);
+        gn = next_bases();
     }
-    // bases of the chunk that is loaded next: fetched (scalar loads) one step before they are needed
-    int64_t gn0 = group_base(k_lo + 2 * kChunk), gn1 = group_base(k_lo + 2 * kChunk + 16);
-    for (int i = 0; i < nch; i += 2) {
-        const int c = k_lo + kChunk * i;
-        int64_t t0 = group_base(c + 3 * kChunk), t1 = group_base(c + 3 * kChunk + 16);
-        consume(ra, c);
-        if (i + 2 < nch) load(ra, gn0, gn1);
-        gn0 = t0, gn1 = t1;
-        finish(c);
-        if (i + 1 < nch) {
-            t0 = group_base(c + 4 * kChunk), t1 = group_base(c + 4 * kChunk + 16);
-            consume(rb, c + kChunk);
-            if (i + 3 < nch) load(rb, gn0, gn1);
-            gn0 = t0, gn1 = t1;
-            finish(c + kChunk);
-        }
+    begin_piece();
+    for (int g = 0; g < nrun; g += 2) {
+        step(ra, g + 2 < nrun);
+        if (g + 1 < nrun) step(rb, g + 3 < nrun);
     }
+}
 
-    // ---- this wave's result: G heads x HD channels, no other wave involved ---------------------------
-    l_run += __shfl_xor(l_run, 16);
-    l_run += __shfl_xor(l_run, 32);
-    if (l16 < G) {
-        const int head = kvh * G + l16;
-        if (partial_base == nullptr) {
-            elem_t *o = (elem_t *)p.out + (int64_t)s * p.o_stride_tok + (int64_t)head * p.o_stride_head;
-            const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                typedef elem_t ex4 __attribute__((ext_vector_type(4)));
-                ex4 w;
-#pragma unroll
-                for (int v = 0; v < 4; ++v) w[v] = (elem_t)(oacc[db][v] * inv);
-                *(ex4 *)(o + db * 16 + 4 * lg) = w;
-            }
-        } else {
-            float *w = partial_base + (int64_t)head * head_stride;
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                // (HD + 2) floats per record: 8-byte aligned, so two 8-byte stores per block of 4
-                *(float2 *)(w + db * 16 + 4 * lg) = float2{oacc[db][0], oacc[db][1]};
-                *(float2 *)(w + db * 16 + 4 * lg + 2) = float2{oacc[db][2], oacc[db][3]};
-            }
-            if (lg == 0) *(float2 *)(w + HD) = float2{m_run, l_run};
+// The result of a part that holds no key (an empty context): zeros as output, or a record with
+// m = -inf and l = 0.  No table entry is touched.
+template <int HD>
+__device__ __forceinline__ void decode_write_empty(const KParams &p, int lane, int s, int kvh, float *partial_base, int64_t head_stride)
+{
+    const int l16 = lane & 15;
+    const int lg = lane >> 4;
+    if (l16 >= p.group) return;
+    const int head = kvh * p.group + l16;
+    if (partial_base == nullptr) {
+        elem_t *o = (elem_t *)p.out + (int64_t)s * p.o_stride_tok + (int64_t)head * p.o_stride_head;
+        for (int d = 4 * lg; d < HD; d += 16) *(uint2 *)(o + d) = uint2{0u, 0u};
+    } else {
+        float *w = partial_base + (int64_t)head * head_stride;
+        for (int d = 4 * lg; d < HD; d += 16) {
+            *(float2 *)(w + d) = float2{0.f, 0.f};
+            *(float2 *)(w + d + 2) = float2{0.f, 0.f};
         }
+        if (lg == 0) *(float2 *)(w + HD) = float2{-INFINITY, 0.f};
     }
 }
 
 // Variant that keeps a whole KV-cache block together: a workgroup owns (sequence, part) and its
 // wavefront w owns KV head w, so the eight 256-byte head slices of a token row are fetched by one
 // workgroup at about the same time (whole 32 KB blocks per 16 keys instead of scattered slices), and
-// no wavefront ever waits for another: there is no barrier and no cross-wave reduction.  About two
-// chunks per wavefront are in flight in registers (two alternating register sets, reloaded as soon
-// as consumed), and block-table entries are read through the scalar cache one step ahead of the
-// loads that need them.
+// no wavefront ever waits for another: there is no barrier and no cross-wave reduction.  A part is a
+// run of chunks inside one sequence (decode_stream_run).
 template <int HD, int WAVES>
 __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void decode_seq_kernel(const KParams p)
 {
@@ -528,8 +581,14 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void decode_seq_kernel(const
     float *partial = p.num_splits == 1 ? nullptr
                                        : p.workspace + ((int64_t)s * p.num_q_heads * p.num_splits + part) * (HD + 2);
     // records of one sequence are laid out [head][part]
-    decode_stream_part<HD, WAVES>(p, lds + wave * C::kVBytes, lane, s, kvh, n_kv, k_lo, k_hi, partial,
-                                  (int64_t)p.num_splits * (HD + 2));
+    const int64_t head_stride = (int64_t)p.num_splits * (HD + 2);
+    if (k_hi <= k_lo) {
+        decode_write_empty<HD>(p, lane, s, kvh, partial, head_stride);
+        return;
+    }
+    decode_stream_run<HD, WAVES>(
+        p, lds + wave * C::kVBytes, lane, kvh, s, k_lo / kChunk, (k_hi - k_lo + kChunk - 1) / kChunk, [&](int, bool) { return partial; },
+        head_stride);
 }
 
 // Merge of the `parts` records of one query head by half a wavefront (32 lanes, all active; `sub` =
@@ -739,27 +798,11 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void decode_balanced_kernel(
 
     const RunStart run = locate_run(p, lane, w, num_wgs, writer, prefix_out);
     if (kvh >= p.num_kv_heads || run.x0 >= run.x1) return;
-    const int x0 = run.x0, x1 = run.x1;
-    int s = run.s, off = run.off;
-
-    // walk the pieces
-    int remaining = x1 - x0;
-    while (remaining > 0) {
-        const int n_kv = p.seq_lens[s];
-        const int nc = (n_kv + kChunk - 1) / kChunk;
-        const int n = remaining < nc - off ? remaining : nc - off;
-        if (n > 0) {
-            const int k_lo = off * kChunk;
-            const int k_hi = (off + n) * kChunk < n_kv ? (off + n) * kChunk : n_kv;
-            // a sequence that lies inside this walk is finished here; a piece of a sequence shared with
-            // other workgroups leaves a record for the merge kernel
-            float *partial = n == nc ? nullptr : p.workspace + (int64_t)(w + s) * p.num_q_heads * (HD + 2);
-            decode_stream_part<HD, WAVES>(p, lds + wave * C::kVBytes, lane, s, kvh, n_kv, k_lo, k_hi, partial, HD + 2);
-            remaining -= n;
-        }
-        ++s;
-        off = 0;
-    }
+    // a sequence that lies inside the run is finished there; a piece of a sequence shared with other
+    // workgroups leaves a record for the merge kernel
+    decode_stream_run<HD, WAVES>(
+        p, lds + wave * C::kVBytes, lane, kvh, run.s, run.off, run.x1 - run.x0,
+        [&](int s, bool whole) { return whole ? nullptr : p.workspace + (int64_t)(w + s) * p.num_q_heads * (HD + 2); }, HD + 2);
 }
 
 // Combine for the token-balanced variant: the pieces of sequence s are the workgroups that overlap its
