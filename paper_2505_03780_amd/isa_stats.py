@@ -88,7 +88,10 @@ def family(kernel: str) -> str:
 
 
 def render(rows) -> str:
-    L = ["## Per kernel", "", "| translation unit | kernel | instructions | distinct opcodes | MFMA | LDS ops | global/buffer loads | VGPRs (of which AGPRs) | SGPRs | static LDS B | scratch B |",
+    L = ["# Static instruction statistics of every compiled kernel instance", "",
+         "Command (no GPU needed; compiles every translation unit to gfx950 assembly with the library's flags):",
+         "`python -m paper_2505_03780_amd.isa_stats --out profiles/instance_isa_stats.md`", "",
+         "## Per kernel", "", "| translation unit | kernel | instructions | distinct opcodes | MFMA | LDS ops | global/buffer loads | VGPRs (of which AGPRs) | SGPRs | static LDS B | scratch B |",
          "|---|---|---|---|---|---|---|---|---|---|---|"]
     for r in sorted(rows, key=lambda r: (r["tu"], r["kernel"])):
         ops = r["ops"]
