@@ -161,6 +161,58 @@ def test_graph_capture_and_replay_matches_eager():
         assert np.array_equal(eager, _bits(dw.out))
 
 
+def test_a_serving_step_of_four_calls_captured_in_one_graph_replays_like_eager():
+    """KV-cache write -> chunked prefill over the written cache -> paged decode -> fused add + RMS norm,
+    recorded into one graph and replayed with eager work and synchronisations between the replays."""
+    rng = np.random.default_rng(63)
+    lens = [700, 130, 64, 1500]
+    wl = W.make_paged(63, "decode", np.ones(4, np.int32), lens, 32, 8, 128, 16, 200)
+    dw = DeviceWorkload(wl)
+    pw = W.make_paged(64, "prefill", [64, 1, 33, 100], lens, 32, 8, 128, 16, 200)
+    pw = W.Workload("chunk", "prefill", "bf16", pw.q, wl.k, wl.v, pw.query_start_loc, wl.seq_lens, wl.scale, True, block_table=wl.block_table,
+                    block_size=16)
+    dp = DeviceWorkload(pw)
+    dp.k, dp.v = dw.k, dw.v  # both attend to the cache that the first call writes into
+    # new keys and values for the last token of every sequence
+    slots = np.array([wl.block_table[s, (n - 1) // 16] * 16 + (n - 1) % 16 for s, n in enumerate(lens)], np.int32)
+    k_new = torch.from_numpy(rng.standard_normal((4, 8, 128)).astype(np.float32)).cuda().to(torch.bfloat16)
+    v_new = torch.from_numpy(rng.standard_normal((4, 8, 128)).astype(np.float32)).cuda().to(torch.bfloat16)
+    d_slots = torch.from_numpy(slots).cuda()
+    weight = torch.from_numpy(rng.standard_normal(32 * 128).astype(np.float32)).cuda().to(torch.bfloat16)
+    res0 = torch.from_numpy(rng.standard_normal((4, 32 * 128)).astype(np.float32)).cuda().to(torch.bfloat16)
+    residual = res0.clone()
+    normed = torch.empty_like(residual)
+    lib = A.load_library()
+    a_dec, a_pre = dw.args(True), dp.args(False)
+
+    def step(stream):
+        A.attn_kv_cache_write(k_new, v_new, dw.k, dw.v, d_slots, stream=stream)
+        assert lib.attn_prefill_varlen(a_pre, stream.cuda_stream) == 0
+        assert lib.attn_decode_paged(a_dec, stream.cuda_stream) == 0
+        A.rmsnorm_fused_add(dw.out.view(4, 32 * 128), weight, normed, 1e-5, residual=residual, stream=stream)
+
+    step(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    want = [_bits(dp.out), _bits(dw.out), _bits(normed), _bits(residual)]
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            step(torch.cuda.current_stream())
+    for _ in range(3):
+        dp.out.fill_(float("nan"))
+        dw.out.fill_(float("nan"))
+        normed.fill_(float("nan"))
+        residual.copy_(res0)  # the norm updates the residual stream in place
+        (dw.k[0, 0, 0, :4] + 1).sum().item()  # eager work and a synchronisation between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = [_bits(dp.out), _bits(dw.out), _bits(normed), _bits(residual)]
+        for name, x, y in zip(("prefill", "decode", "norm", "residual"), want, got):
+            assert np.array_equal(x, y), name
+
+
 def test_debug_validate_catches_bad_device_side_integers():
     """ATTN_DEBUG_VALIDATE is read once per process, so the checks run in a child that has it set."""
     import os
