@@ -98,6 +98,33 @@ def test_benchmark_shape_sampled_rows_and_strided_views():
     assert (big_r[1::2] == 0).all() and (big_r[::2, H:] == 0).all()
 
 
+def test_rows_past_4_gib_in_every_buffer():
+    """300 000 rows of 8192 elements: 4.9 GB per buffer, so the byte offset of most rows needs more than
+    32 bits.  The data is made on the device; the oracle takes a sample of rows (each row is an
+    independent problem), among them the first and the last."""
+    T, H = 300_000, 8192
+    assert T * H * 2 > (1 << 32)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(77)
+    x = torch.empty(T, H, dtype=torch.bfloat16, device="cuda").normal_(generator=g)
+    res = torch.empty(T, H, dtype=torch.bfloat16, device="cuda").normal_(generator=g)
+    w = torch.empty(H, dtype=torch.bfloat16, device="cuda").normal_(generator=g)
+    out = torch.full((T, H), float("nan"), dtype=torch.bfloat16, device="cuda")
+    rows = np.unique(np.concatenate([[0, 1, T - 2, T - 1, (1 << 32) // (2 * H), (1 << 32) // (2 * H) + 1],
+                                     np.random.default_rng(78).integers(0, T, 250)]))
+    idx = torch.from_numpy(rows).cuda()
+    x_s, r_s = _f64(x[idx]), _f64(res[idx])
+    A.rmsnorm_fused_add(x, w, out, 1e-5, residual=res)
+    torch.cuda.synchronize()
+    y_ref, r_ref = oracle.rms_norm(x_s, _f64(w), 1e-5, r_s)
+    _check(_f64(out[idx]), y_ref, "rows past 4 GiB")
+    _check(_f64(res[idx]), r_ref, "rows past 4 GiB, residual")
+    # every row was written: no NaN left anywhere (one pass over the 4.9 GB on the device)
+    assert not bool(torch.isnan(out).any())
+    del x, res, out
+    torch.cuda.empty_cache()
+
+
 def test_in_place_output_zero_rows_large_values_and_errors():
     wl = W.make_rmsnorm(6, 5, 4096, False)
     y_ref, _ = _ref(wl)
