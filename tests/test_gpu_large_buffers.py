@@ -1,4 +1,4 @@
-"""A KV-cache pool beyond 4 GiB: block offsets that do not fit in 32 bits.
+"""Buffers beyond 4 GiB: a KV-cache pool whose block offsets, and a packed batch whose row offsets, do not fit in 32 bits.
 
 The cache of a long-context server on a 288 GB device is far larger than any pool the parity tests
 build on the host, so the 64-bit part of the kernels' address arithmetic (block index x block stride)
@@ -109,3 +109,43 @@ def test_kv_cache_write_reaches_slots_past_4_gib(big_pools):
     oracle.kv_cache_write(kc, vc, kn, vn, np.arange(T, dtype=np.int32))
     np.testing.assert_array_equal(got_k, kc[:, 0])
     np.testing.assert_array_equal(got_v, vc[:, 0])
+
+
+def test_packed_prefill_whose_rows_lie_past_4_gib():
+    """9000 packed sequences of 30-90 tokens: 540 000 query rows x 32 heads x 128 = 4.4 GB of Q and of
+    output, so the row offsets of most sequences need more than 32 bits.  The data is made on the
+    device; the oracle gets a sample of whole sequences (the first, the last, the ones around the
+    4 GiB mark and 60 drawn at random), each an independent problem."""
+    rng = np.random.default_rng(75)
+    lens = rng.integers(30, 91, 9000).astype(np.int32)
+    qsl = np.zeros(len(lens) + 1, np.int32)
+    qsl[1:] = np.cumsum(lens)
+    total = int(qsl[-1])
+    Hq = 32
+    assert total * Hq * D * 2 > (1 << 32)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(76)
+    q = torch.empty(total, Hq, D, dtype=torch.bfloat16, device="cuda").normal_(generator=g)
+    k = torch.empty(total, HKV, D, dtype=torch.bfloat16, device="cuda").normal_(generator=g)
+    v = torch.empty(total, HKV, D, dtype=torch.bfloat16, device="cuda").normal_(generator=g)
+    out = torch.full_like(q, float("nan"))
+    d_qsl, d_lens = torch.from_numpy(qsl).cuda(), torch.from_numpy(lens).cuda()
+    scale = float(np.float32(1.0 / np.sqrt(np.float32(D))))
+    A.attn_prefill_varlen(q, k, v, out, d_qsl, d_lens, scale, max_q_len=int(lens.max()), max_kv_len=int(lens.max()), kv_start_loc=d_qsl)
+    torch.cuda.synchronize()
+    assert not bool(torch.isnan(out).any()), "a row was not written"
+    mark = int(np.searchsorted(qsl, (1 << 32) // (Hq * D * 2)))
+    seqs = np.unique(np.concatenate([[0, 1, mark - 1, mark, mark + 1, len(lens) - 2, len(lens) - 1], rng.integers(0, len(lens), 60)]))
+    seqs = seqs[(seqs >= 0) & (seqs < len(lens))]
+    rows = np.concatenate([np.arange(qsl[s], qsl[s + 1]) for s in seqs])
+    idx = torch.from_numpy(rows).cuda()
+
+    def bits(t):
+        return t[idx].view(torch.int16).cpu().numpy().view(np.uint16)
+
+    sub_lens = lens[seqs]
+    sub_qsl = np.zeros(len(seqs) + 1, np.int32)
+    sub_qsl[1:] = np.cumsum(sub_lens)
+    sub = W.Workload("sample", "prefill", "bf16", bits(q), bits(k), bits(v), sub_qsl, sub_lens.copy(), scale, True, kv_start_loc=sub_qsl.copy())
+    ref = oracle.attention(oracle_problem(sub))
+    assert_close(to_host_f64(out[idx]), ref, "bf16", "sampled sequences of a 4.4 GB packed batch")
