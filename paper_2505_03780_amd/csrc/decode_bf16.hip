@@ -20,6 +20,13 @@
 //    chunk's loads are issued before the current chunk is consumed.
 //  * Each part leaves an fp32 (partial output, max, sum) triple per query head;
 //    a second kernel merges the parts, one wavefront per (sequence, head).
+//
+// Three kernels share these pieces (each is described where it is defined):
+// decode_bf16_kernel, the one sketched above; decode_seq_kernel, one wavefront
+// per KV head so that a workgroup fetches whole cache blocks; and
+// decode_balanced_kernel, which deals the batch's 32-key chunks out evenly over
+// one workgroup per compute unit whatever the mix of lengths.  The last two
+// stream through decode_stream_run.
 #include "kernel_params.hpp"
 
 namespace attn {
