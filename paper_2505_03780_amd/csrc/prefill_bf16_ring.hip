@@ -287,9 +287,24 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
     const int dma_row = RPW * wave + (lane >> 4);  // + 4*i, row inside the unit
     const uint32_t tok_bytes = (uint32_t)p.kv_stride_tok * 2;
     const int last_unit0 = (n_kv - 1) & ~(kUnit - 1);  // first key of the last unit that holds a real key
-    uint32_t dma_chunk_off[NDMA];
+    // Per-lane byte offset of a transfer from the first row of this wave's share of a unit: the lane's
+    // row and its swizzled 16-byte chunk.  It is the same in every unit whose rows all exist; in a
+    // ragged last unit (and in the repeats of it past the end) the rows past the end re-read the last
+    // key (finite, masked), which gives a second set of offsets.  Everything else about a transfer's
+    // address is wave-uniform: scalar arithmetic.
+    uint32_t dma_off[NDMA], dma_off_last[NDMA];
+    const uint32_t block_bytes = (uint32_t)(p.kv_stride_block * 2);  // (ring_valid checks that it fits)
+    {
+        const int wrow_last = last_unit0 + RPW * wave < n_kv ? last_unit0 + RPW * wave : n_kv - 1;
 #pragma unroll
-    for (int i = 0; i < NDMA; ++i) dma_chunk_off[i] = 16 * ((lane & 15) ^ swz(dma_row + 4 * i));
+        for (int i = 0; i < NDMA; ++i) {
+            const uint32_t chunk = 16 * ((lane & 15) ^ swz(dma_row + 4 * i));
+            dma_off[i] = (uint32_t)((lane >> 4) + 4 * i) * tok_bytes + chunk;
+            int row = last_unit0 + dma_row + 4 * i;
+            row = row < n_kv ? row : n_kv - 1;
+            dma_off_last[i] = (uint32_t)(row - wrow_last) * tok_bytes + chunk;
+        }
+    }
     // wave-uniform table entry of the block that holds this wave's rows of `unit` (clamped to the sequence)
     auto table_entry = [&](int unit) -> int {
         if (!PAGED) return 0;
@@ -313,24 +328,19 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
     auto issue_unit = [&](int unit, int entry) {
         unsigned char *slot = lds + (unit % NSLOT) * kSlotBytes + RPW * wave * 256;
         const int u0 = unit * kUnit < last_unit0 ? unit * kUnit : last_unit0;  // units past the end repeat the last one
-        // uniform part
-        int64_t base;
-        int first_row;  // key index that a per-lane row offset of 0 stands for
-        if (PAGED) {
-            int wrow = u0 + RPW * wave;
-            wrow = wrow < n_kv ? wrow : n_kv - 1;
-            first_row = wrow & ~(p.block_size - 1);
-            base = (int64_t)entry * p.kv_stride_block * 2;
-        } else {
-            first_row = u0;
-            base = (int64_t)(kv0 + u0) * tok_bytes;
-        }
+        const bool ragged = u0 + kUnit > n_kv;
+        int wrow = u0 + RPW * wave;  // first row of this wave's share
+        wrow = wrow < n_kv ? wrow : n_kv - 1;
+        // the rows of a wave never straddle a 16-key block: one table entry (PAGED) or one packed run of rows
+        const uint64_t base = PAGED ? (uint64_t)(uint32_t)entry * block_bytes + (uint32_t)(wrow & (p.block_size - 1)) * tok_bytes
+                                    : (uint64_t)(kv0 + wrow) * tok_bytes;
         const unsigned char *kb = kbase + base, *vb = vbase + base;
 #pragma unroll
         for (int i = 0; i < NDMA; ++i) {
-            int row = u0 + dma_row + 4 * i;
-            row = row < n_kv ? row : n_kv - 1;  // rows past the end re-read the last key (finite, masked)
-            const uint32_t o = (uint32_t)(row - first_row) * tok_bytes + dma_chunk_off[i];
+            uint32_t o = ragged ? dma_off_last[i] : dma_off[i];
+            // (kept opaque: a loop-invariant offset would be widened and added to the array bases once, and
+            // the transfers would then carry 64-bit per-lane addresses instead of scalar base + 32-bit offset)
+            asm volatile("" : "+v"(o));
             __builtin_amdgcn_global_load_lds((gbl_void *)(kb + o), (lds_void *)(slot + 4 * i * 256), 16, 0, 0);
             __builtin_amdgcn_global_load_lds((gbl_void *)(vb + o), (lds_void *)(slot + kVOff + 4 * i * 256), 16, 0, 0);
         }
@@ -352,20 +362,24 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
     // (ds_read_b64_tr_b16, the slow path) and stores them in MFMA A-operand order; every wave then
     // fetches all eight fragments with plain 128-bit reads.  Two images alternate.
     unsigned char *img_base = lds + NSLOT * kSlotBytes;
+    // where inside a slot each of this lane's transposing reads goes (the same in every unit)
+    int tr_off[C::kFragsPerWave][2];
+#pragma unroll
+    for (int i = 0; i < C::kFragsPerWave; ++i) {
+        const int f = wave * C::kFragsPerWave + i;  // f = ks2 * DB + db
+        const int db = f % DB, ks2 = f / DB;
+        const int a = l16 >> 2, h1 = (lane >> 4) & 1, h0 = (lane & 3) >> 1;
+#pragma unroll
+        for (int rd = 0; rd < 2; ++rd)
+            tr_off[i][rd] = kVOff + (8 * rd + 4 * lhalf + a) * 256 + 16 * (((db ^ a) << 2) | (2 * (h1 ^ rd)) | (h0 ^ lhalf)) + 8 * (lane & 1) +
+                            ks2 * 16 * 256;
+    }
     auto transpose_load = [&](int unit, s16x4 (&raw)[C::kFragsPerWave][2]) {
         const unsigned char *vt = lds + (unit % NSLOT) * kSlotBytes;
 #pragma unroll
         for (int i = 0; i < C::kFragsPerWave; ++i) {
-            const int f = wave * C::kFragsPerWave + i;  // f = ks2 * DB + db
-            const int db = f % DB, ks2 = f / DB;
-            // voff is indexed with a compile-time db in the main loop; here db depends on the wave
-            const int a = l16 >> 2, h1 = (lane >> 4) & 1, h0 = (lane & 3) >> 1;
 #pragma unroll
-            for (int rd = 0; rd < 2; ++rd) {
-                const int o = kVOff + (8 * rd + 4 * lhalf + a) * 256 + 16 * (((db ^ a) << 2) | (2 * (h1 ^ rd)) | (h0 ^ lhalf)) +
-                              8 * (lane & 1) + ks2 * 16 * 256;
-                raw[i][rd] = lds_read_tr16_b64_untracked(vt + o);
-            }
+            for (int rd = 0; rd < 2; ++rd) raw[i][rd] = lds_read_tr16_b64_untracked(vt + tr_off[i][rd]);
         }
     };
     auto transpose_store = [&](int unit, s16x4 (&raw)[C::kFragsPerWave][2]) {
@@ -530,8 +544,6 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
         u32x4 vfrag[2 * DB];
         s16x4 raw[C::kFragsPerWave][2];
         float sum[QB][2];
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) sum[qb][0] = sum[qb][1] = 0.f;
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         int seq = 0;        // LDS operations issued so far in this iteration
         int vpos[2 * DB];   // position of image fragment f in this iteration's sequence
@@ -551,7 +563,7 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
             // instruction that would sum the rounded pair in one go occupies the matrix pipe for about
             // half an MFMA (measured), so it is not free under the MFMAs; the sum of the unrounded
             // weights differs from the sum of the rounded ones by rounding errors that average out.
-            sum[qb][pair & 1] += e0 + e1;
+            sum[qb][pair & 1] = pair < 2 ? e0 + e1 : sum[qb][pair & 1] + (e0 + e1);  // pairs come in order: 0 and 1 start the chains
             pf[qb][v >> 3][v & 7] = pr[0];
             pf[qb][v >> 3][(v & 7) + 1] = pr[1];
         };
@@ -722,7 +734,8 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
 template <typename E, int QB, int HPW, int NSLOT, int PF, int WAVES>
 bool ring_valid(const KParams &p)
 {
-    return p.dtype == E::kDtype && p.head_dim == kHD && p.group % HPW == 0;
+    // (a cache block of 4 GiB or more would need 64-bit block arithmetic in the transfers)
+    return p.dtype == E::kDtype && p.head_dim == kHD && p.group % HPW == 0 && (!p.block_table || (uint64_t)p.kv_stride_block * 2 < (1ull << 32));
 }
 
 template <typename E, int QB, int HPW, int NSLOT, int PF, int WAVES, bool PAGED>
