@@ -552,10 +552,19 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
         // weights 2p, 2p+1 of row block qb: exponentials, rounding, row sum.  The exponentials are spread over
         // both phases (half under the score MFMAs, half under the first PV MFMAs, which only need the
         // first half), so that neither phase has more vector work than matrix work to hide it under.
-        auto exp_pair = [&](int qb, int pair) {
+        // Two steps, a group apart: the exponentials are issued under one MFMA and their results are
+        // rounded and summed under the next, so that nothing waits for the transcendental unit's
+        // latency (a wavefront issues in order: a use right behind the exponential stalls it).
+        float e_pending[QB][2];
+        auto exp_issue = [&](int qb, int pair) {
             const int v = 2 * pair;
-            const float e0 = fast_exp2(CUR_MASK ? cur[qb][v] - m_ref[qb] : __builtin_fmaf(cur[qb][v], c, -m_ref[qb]));
-            const float e1 = fast_exp2(CUR_MASK ? cur[qb][v + 1] - m_ref[qb] : __builtin_fmaf(cur[qb][v + 1], c, -m_ref[qb]));
+            e_pending[qb][0] = fast_exp2(CUR_MASK ? cur[qb][v] - m_ref[qb] : __builtin_fmaf(cur[qb][v], c, -m_ref[qb]));
+            e_pending[qb][1] = fast_exp2(CUR_MASK ? cur[qb][v + 1] - m_ref[qb] : __builtin_fmaf(cur[qb][v + 1], c, -m_ref[qb]));
+            asm volatile("" : "+v"(e_pending[qb][0]), "+v"(e_pending[qb][1]));  // issued here, not where they are used
+        };
+        auto exp_finish = [&](int qb, int pair) {
+            const int v = 2 * pair;
+            const float e0 = e_pending[qb][0], e1 = e_pending[qb][1];
             x2 pr;
             pr[0] = (elem)e0;
             pr[1] = (elem)e1;
@@ -574,7 +583,12 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
             // kXOps + 8; since then the rest of that iteration and `seq` operations of this one were issued
             if (qb == 0) lds_wait_upto((KSTEPS - 1 - ks) + seq, kf[ks]);
             nxt[qb] = E::mfma(__builtin_bit_cast(x8, kf[ks]), qf[qb][ks], ks == 0 ? zero : nxt[qb]);
-            if (ks % 2 == 0) exp_pair(qb, ks / 2);  // weights of keys 0..15: the B operand of the first four PV MFMAs
+            // weights of keys 0..15 (the B operand of the first four PV MFMAs): issued under the even steps,
+            // finished under the odd ones
+            if (ks % 2 == 0)
+                exp_issue(qb, ks / 2);
+            else
+                exp_finish(qb, ks / 2);
             if (g * 8 / G != (g + 1) * 8 / G) {
                 const int f = g * 8 / G;
                 switch (f) {  // the fragment index becomes the instruction's immediate offset
@@ -614,9 +628,12 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const int f = g / QB, qb = g % QB;  // f = ks2 * DB + db
+            // weights of keys 16..31, needed from the fifth PV MFMA on: each pair is finished a group after
+            // it was issued (the last one just ahead of the MFMA that needs it)
+            if (f >= 1 && f <= DB) exp_finish(qb, 3 + f);
             if (qb == 0) lds_wait_upto(seq - 1 - vpos[f], vfrag[f]);
             oacc[qb][f % DB] = E::mfma(__builtin_bit_cast(x8, vfrag[f]), pf[qb][f / DB], oacc[qb][f % DB]);
-            if (f < DB) exp_pair(qb, 4 + f);  // weights of keys 16..31, needed from the fifth PV MFMA on
+            if (f < DB) exp_issue(qb, 4 + f);
             const int sl = g - 4 * QB;  // the second half of the phase: the last S MFMAs have drained
             if (sl >= 0 && sl < 4 * QB) {
                 const int q2 = sl / 4, v0 = 4 * (sl % 4);
