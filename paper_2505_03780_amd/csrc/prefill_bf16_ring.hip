@@ -432,24 +432,28 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
     };
     // Move the reference of the rows whose new maximum outgrew it by more than the slack; rare, and
     // wave-uniform, so the accumulators are only touched when needed.
-    auto move_reference = [&](const float (&bm)[QB]) {
+    auto reference_outgrown = [&](const float (&bm)[QB]) -> bool {
         bool grow = false;
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) grow |= bm[qb] > m_ref[qb] + kSlack;
-        if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+        return __builtin_amdgcn_ballot_w64(grow) != 0;
+    };
+    auto rescale_to = [&](const float (&bm)[QB]) {
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                float m_new = fmaxf(m_ref[qb], bm[qb]);
-                m_new = m_new == -INFINITY ? 0.f : m_new;
-                const float alpha = fast_exp2(m_ref[qb] - m_new);
-                m_ref[qb] = m_new;
-                l_run[qb] *= alpha;
+        for (int qb = 0; qb < QB; ++qb) {
+            float m_new = fmaxf(m_ref[qb], bm[qb]);
+            m_new = m_new == -INFINITY ? 0.f : m_new;
+            const float alpha = fast_exp2(m_ref[qb] - m_new);
+            m_ref[qb] = m_new;
+            l_run[qb] *= alpha;
 #pragma unroll
-                for (int db = 0; db < DB; ++db)
+            for (int db = 0; db < DB; ++db)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) oacc[qb][db][v] *= alpha;
-            }
+                for (int v = 0; v < 16; ++v) oacc[qb][db][v] *= alpha;
         }
+    };
+    auto move_reference = [&](const float (&bm)[QB]) {
+        if (reference_outgrown(bm)) rescale_to(bm);
     };
     // Row maxima of a fresh score tile (masked if MASK), then move the reference if a row outgrew it.
     // With MASK the tile is left scaled (x = c*s, masked entries -inf); without, it stays raw.
@@ -621,7 +625,8 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
             __builtin_amdgcn_sched_barrier(0);
         }
 
-        float mx[QB];
+        float mx[QB], bm[QB];
+        bool outgrown = false;
         int rel[QB];
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) rel[qb] = qrel[qb] - (u + 1) * kUnit;
@@ -634,18 +639,31 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
             if (qb == 0) lds_wait_upto(seq - 1 - vpos[f], vfrag[f]);
             oacc[qb][f % DB] = E::mfma(__builtin_bit_cast(x8, vfrag[f]), pf[qb][f / DB], oacc[qb][f % DB]);
             if (f < DB) exp_issue(qb, 4 + f);
-            const int sl = g - 4 * QB;  // the second half of the phase: the last S MFMAs have drained
-            if (sl >= 0 && sl < 4 * QB) {
-                const int q2 = sl / 4, v0 = 4 * (sl % 4);
+            // The second half of the phase (the last S MFMAs have drained) has vector slots to spare: the row
+            // maxima of S(u+1), eight scores per group, and right behind them the test whether a reference
+            // has to move, so that the answer is there when the last MFMA of the iteration has been issued.
+            const int sl = g - 4 * QB;
+            if (sl >= 0 && sl < 2 * QB) {
+                const int q2 = sl / 2, v0 = 8 * (sl % 2);
                 if (NXT_MASK) {
 #pragma unroll
-                    for (int v = v0; v < v0 + 4; ++v) {
+                    for (int v = v0; v < v0 + 8; ++v) {
                         const float x = nxt[q2][v] * c;
                         nxt[q2][v] = (8 * (v >> 2) + (v & 3)) > rel[q2] ? -INFINITY : x;
                     }
                 }
-                const float m3 = fmaxf(fmaxf(nxt[q2][v0], nxt[q2][v0 + 1]), nxt[q2][v0 + 2]);
-                mx[q2] = v0 == 0 ? fmaxf(m3, nxt[q2][v0 + 3]) : fmaxf(fmaxf(mx[q2], m3), nxt[q2][v0 + 3]);
+                float m3 = fmaxf(fmaxf(nxt[q2][v0], nxt[q2][v0 + 1]), nxt[q2][v0 + 2]);
+                m3 = fmaxf(fmaxf(m3, nxt[q2][v0 + 3]), nxt[q2][v0 + 4]);
+                m3 = fmaxf(fmaxf(m3, nxt[q2][v0 + 5]), nxt[q2][v0 + 6]);
+                mx[q2] = v0 == 0 ? fmaxf(m3, nxt[q2][v0 + 7]) : fmaxf(fmaxf(mx[q2], m3), nxt[q2][v0 + 7]);
+            }
+            if (sl == 2 * QB) {
+#pragma unroll
+                for (int q2 = 0; q2 < QB; ++q2) {
+                    const float m = swap32_max(mx[q2]);
+                    bm[q2] = NXT_MASK ? m : m * c;
+                }
+                outgrown = reference_outgrown(bm);
             }
             // K fragments of unit u+2 (the fragments of u+1 were consumed in phase X), in order, early in
             // the phase: they are a few groups old when the next iteration asks for them
@@ -662,13 +680,7 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
         }
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) l_run[qb] += sum[qb][0] + sum[qb][1];
-        float bm[QB];
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            const float m = swap32_max(mx[qb]);
-            bm[qb] = NXT_MASK ? m : m * c;
-        }
-        move_reference(bm);
+        if (outgrown) rescale_to(bm);
         // Publish.  This wave's transfers of every unit but the newest PF-3 have landed (see ring_barrier);
         // its image stores have been performed (phase Y waited for younger reads); its K reads may still
         // be in flight, they target a slot that no transfer touches before the barrier after next.
