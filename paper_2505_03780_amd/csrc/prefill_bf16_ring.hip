@@ -536,9 +536,21 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
     // requested (scalar cache) at the top of an iteration, awaited at its barrier -- the one place where
     // this wave waits for everything it has in flight, because scalar loads share the LDS counter and
     // return out of order.
-    auto iteration = [&](int u, f32x16 (&cur)[QB], f32x16 (&nxt)[QB], auto cur_tag, auto nxt_tag) {
+    // LDS addresses of this lane's K fragment reads inside slot 0, and the same 64 KiB further on: with
+    // the slot known at compile time (the plain units' loop below is unrolled over the ring) the slot
+    // becomes the read's 16-bit immediate offset instead of an addition per read.
+    unsigned kaddr[KSTEPS], kaddr_far[KSTEPS];
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+        kaddr[ks] = lds_addr(lds + koff[ks]);
+        kaddr_far[ks] = kaddr[ks] + 65536u;
+        if (NSLOT > 4) asm volatile("" : "+v"(kaddr_far[ks]));  // a register of its own, not an addition at every use
+    }
+    // SLOT2 >= 0: the ring slot of unit u+2, known at compile time
+    auto iteration = [&](int u, f32x16 (&cur)[QB], f32x16 (&nxt)[QB], auto cur_tag, auto nxt_tag, auto slot_tag) {
         constexpr bool CUR_MASK = decltype(cur_tag)::value;
         constexpr bool NXT_MASK = decltype(nxt_tag)::value;
+        constexpr int SLOT2 = decltype(slot_tag)::value;
         constexpr int G = 8 * QB;  // MFMAs per product
         const unsigned img_rd = lds_addr(img_base + (u & 1) * C::kImgBytes + lane * 16);
         const unsigned img_wr = lds_addr(img_base + ((u + 1) & 1) * C::kImgBytes + lane * 16);
@@ -671,7 +683,10 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
             for (int j = 0; j < kKPerGroup; ++j) {
                 const int ks = g * kKPerGroup + j;
                 if (ks < KSTEPS) {
-                    kf[ks] = lds_read_b128_untracked<0>(lds_addr(kt2 + koff[ks]));
+                    if (SLOT2 < 0)
+                        kf[ks] = lds_read_b128_untracked<0>(lds_addr(kt2 + koff[ks]));
+                    else
+                        kf[ks] = lds_read_b128_untracked<(SLOT2 < 0 ? 0 : SLOT2 % 4) * kSlotBytes>(SLOT2 >= 4 ? kaddr_far[ks] : kaddr[ks]);
                     ++seq;
                 }
             }
@@ -695,26 +710,42 @@ __global__ __launch_bounds__(WAVES * 64, (QB == 1 && WAVES == 4) ? 2 : 1) void p
         for (int qb = 0; qb < QB; ++qb) s_cur[qb] = s_nxt[qb];
     };
     int u = 0;
-    // plain units whose successor is plain too, two per trip so that the two score tiles swap roles
+    using AnySlot = std::integral_constant<int, -1>;
+    // plain units whose successors are plain too, one trip round the ring per pass (u is a multiple of
+    // NSLOT here, so unit u+2+i sits in slot (2+i) % NSLOT)
+    for (; u + NSLOT < first_masked; u += NSLOT) {
+        iteration(u, s_cur, s_nxt, Plain{}, Plain{}, std::integral_constant<int, 2 % NSLOT>{});
+        iteration(u + 1, s_nxt, s_cur, Plain{}, Plain{}, std::integral_constant<int, 3 % NSLOT>{});
+        iteration(u + 2, s_cur, s_nxt, Plain{}, Plain{}, std::integral_constant<int, 4 % NSLOT>{});
+        iteration(u + 3, s_nxt, s_cur, Plain{}, Plain{}, std::integral_constant<int, 5 % NSLOT>{});
+        if (NSLOT == 8) {
+            iteration(u + 4, s_cur, s_nxt, Plain{}, Plain{}, std::integral_constant<int, 6 % NSLOT>{});
+            iteration(u + 5, s_nxt, s_cur, Plain{}, Plain{}, std::integral_constant<int, 7 % NSLOT>{});
+            iteration(u + 6, s_cur, s_nxt, Plain{}, Plain{}, std::integral_constant<int, 8 % NSLOT>{});
+            iteration(u + 7, s_nxt, s_cur, Plain{}, Plain{}, std::integral_constant<int, 9 % NSLOT>{});
+        }
+    }
+    static_assert(NSLOT == 4 || NSLOT == 8, "the loop above is written out for rings of four and eight slots");
+    // the rest of them, two per trip so that the two score tiles swap roles
     for (; u + 2 < first_masked; u += 2) {
-        iteration(u, s_cur, s_nxt, Plain{}, Plain{});
-        iteration(u + 1, s_nxt, s_cur, Plain{}, Plain{});
+        iteration(u, s_cur, s_nxt, Plain{}, Plain{}, AnySlot{});
+        iteration(u + 1, s_nxt, s_cur, Plain{}, Plain{}, AnySlot{});
     }
     if (u + 1 < first_masked) {
-        iteration(u, s_cur, s_nxt, Plain{}, Plain{});
+        iteration(u, s_cur, s_nxt, Plain{}, Plain{}, AnySlot{});
         copy_back();
         ++u;
     }
     if (!cur_masked) {  // the last plain unit: its successor (if any) is masked
-        iteration(u, s_cur, s_nxt, Plain{}, Masked{});
+        iteration(u, s_cur, s_nxt, Plain{}, Masked{}, AnySlot{});
         copy_back();
         ++u;
     }
     for (; u + 1 < n_units; u += 2) {
-        iteration(u, s_cur, s_nxt, Masked{}, Masked{});
-        iteration(u + 1, s_nxt, s_cur, Masked{}, Masked{});
+        iteration(u, s_cur, s_nxt, Masked{}, Masked{}, AnySlot{});
+        iteration(u + 1, s_nxt, s_cur, Masked{}, Masked{}, AnySlot{});
     }
-    if (u < n_units) iteration(u, s_cur, s_nxt, Masked{}, Masked{});
+    if (u < n_units) iteration(u, s_cur, s_nxt, Masked{}, Masked{}, AnySlot{});
     // The last iteration's K reads are still in flight and nobody will use them: wait for them here,
     // with their registers tied, so that the compiler cannot hand those registers to anything else
     // while a read may still land in them.
