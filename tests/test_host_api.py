@@ -130,6 +130,10 @@ def test_instance_tables_and_heuristic_selection():
     assert names_p[i] == "prefill_bf16_ring d128 qb1 w8 hpw4 slots8 pf8 seqmajor"
     i = A.attn_selected_instance(_args(max_kv_len=8192, max_q_len=8192), False)
     assert names_p[i] == "prefill_bf16_ring d128 qb1 w8 hpw4 slots8 pf5 seqmajor"
+    # a cache whose blocks lie 4 GiB or more apart: the ring kernel's transfers do their block arithmetic
+    # in 32 bits, so the choice falls to the register-staged kernel
+    i = A.attn_selected_instance(_paged(max_kv_len=8704, max_q_len=512, block_table_stride=544, kv_stride_block=1 << 31, num_blocks=4), False)
+    assert "ring" not in names_p[i] and "d128" in names_p[i]
     # MHA cannot
     i = A.attn_selected_instance(_args(num_kv_heads=32), False)
     assert "hpw1" in names_p[i]
