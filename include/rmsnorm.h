@@ -51,8 +51,10 @@ int rmsnorm_fused_add(const rmsnorm_args *args, void *hip_stream);
 
 /* Ahead-of-time tuning for the shape bucket of `shape_like` (hidden size, residual or not, token
  * count rounded up to a power of two): times every valid compiled instance on synthetic buffers that
- * the call allocates and frees, keeps the fastest and, if cache_path is not NULL, merges it into the
- * same cache file attn_tune uses.  `iters` timed launches per instance (<= 0: a default).
+ * the call allocates and frees, then times the three fastest and the built-in choice again taking
+ * turns launch by launch, keeps the fastest of those (the built-in choice keeps ties within 3 %) and,
+ * if cache_path is not NULL, merges it into the same cache file attn_tune uses.  `iters` timed
+ * launches per instance and pass (<= 0: a default).
  * Synchronous; not capturable.  flags: bit 0 = one line per instance on stderr. */
 int rmsnorm_tune(const rmsnorm_args *shape_like, const char *cache_path, int iters, int flags);
 

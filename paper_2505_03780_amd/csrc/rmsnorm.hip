@@ -341,8 +341,24 @@ int tune(const rmsnorm_args *shape, const char *cache_path, int iters, int flags
         release();
         return ATTN_ERR_HIP;
     }
-    int best = -1;
-    double best_us = 0.0;
+    // one timed call; negative on failure
+    auto time_once = [&](int id) -> double {
+        float ms = 0.f;
+        (void)hipEventRecord(e0, 0);
+        const bool ok = run(&a, 0, id) == ATTN_OK;
+        (void)hipEventRecord(e1, 0);
+        if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess || !ok) {
+            (void)hipGetLastError();
+            return -1.0;
+        }
+        return 1000.0 * ms;
+    };
+    auto median = [](std::vector<double> &v) {
+        std::sort(v.begin(), v.end());
+        return v[v.size() / 2];
+    };
+    // First pass: every valid instance on its own, median of `iters` calls.
+    std::vector<std::pair<double, int>> ranked;
     for (int id = 0; id < kNumInstances; ++id) {
         if (!rms_valid(kInstances[id], a.hidden)) continue;
         bool fail = false;
@@ -351,23 +367,50 @@ int tune(const rmsnorm_args *shape, const char *cache_path, int iters, int flags
             (void)hipGetLastError();
             continue;
         }
-        std::vector<float> ms(iters);
-        for (int i = 0; i < iters && !fail; ++i) {
-            (void)hipEventRecord(e0, 0);
-            fail = run(&a, 0, id) != ATTN_OK;
-            (void)hipEventRecord(e1, 0);
-            if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms[i], e0, e1) != hipSuccess) fail = true;
-        }
-        if (fail) {
-            (void)hipGetLastError();
-            continue;
-        }
-        std::sort(ms.begin(), ms.end());
-        const double us = 1000.0 * ms[iters / 2];
-        if (flags & 1) fprintf(stderr, "[rmsnorm_tune] %s :: %-36s %10.2f us\n", key.c_str(), kInstances[id].name, us);
-        if (best < 0 || us < best_us) {
-            best = id;
-            best_us = us;
+        std::vector<double> us(iters);
+        for (int i = 0; i < iters && !fail; ++i) fail = (us[i] = time_once(id)) < 0.0;
+        if (fail) continue;
+        const double m = median(us);
+        if (flags & 1) fprintf(stderr, "[rmsnorm_tune] %s :: %-36s %10.2f us\n", key.c_str(), kInstances[id].name, m);
+        ranked.push_back({m, id});
+    }
+    // Final: the three fastest and the built-in choice are measured again taking turns call by call
+    // (instances measured minutes apart see different clocks); the built-in choice keeps ties within 3 %.
+    int best = -1;
+    double best_us = 0.0;
+    if (!ranked.empty()) {
+        std::sort(ranked.begin(), ranked.end());
+        std::vector<int> finalists;
+        for (size_t i = 0; i < ranked.size() && i < 3; ++i) finalists.push_back(ranked[i].second);
+        const int builtin = heuristic(&a);
+        if (builtin >= 0 && rms_valid(kInstances[builtin], a.hidden) && std::find(finalists.begin(), finalists.end(), builtin) == finalists.end())
+            finalists.push_back(builtin);
+        std::vector<std::vector<double>> turns(finalists.size());
+        bool fail = false;
+        for (int i = 0; i < iters && !fail; ++i)
+            for (size_t f = 0; f < finalists.size() && !fail; ++f) {
+                const double t = time_once(finalists[f]);
+                fail = t < 0.0;
+                turns[f].push_back(t);
+            }
+        if (fail) {  // keep the first pass's answer
+            best = ranked[0].second;
+            best_us = ranked[0].first;
+        } else {
+            double builtin_us = -1.0;
+            for (size_t f = 0; f < finalists.size(); ++f) {
+                const double m = median(turns[f]);
+                if (flags & 1) fprintf(stderr, "[rmsnorm_tune] %s :: final %-30s %10.2f us\n", key.c_str(), kInstances[finalists[f]].name, m);
+                if (finalists[f] == builtin) builtin_us = m;
+                if (best < 0 || m < best_us) {
+                    best = finalists[f];
+                    best_us = m;
+                }
+            }
+            if (builtin_us > 0.0 && best != builtin && best_us > 0.97 * builtin_us) {
+                best = builtin;
+                best_us = builtin_us;
+            }
         }
     }
     (void)hipEventDestroy(e0);
